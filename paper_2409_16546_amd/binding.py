@@ -1,0 +1,233 @@
+"""ctypes binding of the C ABI in ``include/akv.h`` -- argument marshalling only.
+
+Every function has the name of its C entry point and hands torch device pointers and the current
+HIP stream to it; no step of the path runs here.  If ``libakv.so`` has not been built the import of
+the library fails loudly: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libakv.so")
+
+AKV_OK, AKV_EINVAL, AKV_EWORKSPACE, AKV_EHIP = 0, 1, 2, 3
+AKV_TB = 256
+AKV_NFLAGS = 4
+AKV_MAX_TOPK = 64
+EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append",
+           "akv_decode_attention", "akv_unpack", "akv_fp16_decode_attention"]
+
+
+class AkvError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"akv status {status}: {msg}")
+        self.status = status
+
+
+class akv_shape(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("Ncap", C.c_int32)]
+
+
+class akv_sizes(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("k_hi", "k_mid", "k_lo", "v_hi", "v_mid", "v_lo", "colmax", "lens", "flags",
+                                          "workspace", "fp16_workspace")]
+
+
+class akv_cache(C.Structure):
+    _fields_ = [("shape", akv_shape)] + [(n, C.c_void_p) for n in ("k_hi", "k_mid", "k_lo", "v_hi", "v_mid", "v_lo",
+                                                                   "colmax", "lens", "flags")]
+
+
+class akv_debug(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("lvlK", "logits", "a", "sel", "oest", "Ehat", "needV", "appliedV")]
+
+
+class akv_params(C.Structure):
+    _fields_ = [("scale", C.c_float), ("topk", C.c_int32), ("guard_bits", C.c_int32), ("force_level", C.c_int32),
+                ("out_dtype", C.c_int32), ("max_len", C.c_int32), ("dbg", C.POINTER(akv_debug))]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libakv.so (built by ``python -m paper_2409_16546_amd.build`` / ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build the HIP library first (python -m paper_2409_16546_amd.build); "
+                              "there is no CPU fallback")
+        L = C.CDLL(LIB_PATH)
+        L.akv_version.restype = C.c_int
+        L.akv_last_error.restype = C.c_char_p
+        L.akv_layout_sizes.restype = C.c_int
+        L.akv_layout_sizes.argtypes = [C.POINTER(akv_shape), C.POINTER(akv_sizes)]
+        L.akv_cache_reset.restype = C.c_int
+        L.akv_cache_reset.argtypes = [C.POINTER(akv_cache), C.c_void_p]
+        L.akv_append.restype = C.c_int
+        L.akv_append.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.akv_decode_attention.restype = C.c_int
+        L.akv_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.POINTER(akv_params), C.c_void_p,
+                                           C.c_size_t, C.c_void_p]
+        L.akv_unpack.restype = C.c_int
+        L.akv_unpack.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.akv_fp16_decode_attention.restype = C.c_int
+        L.akv_fp16_decode_attention.argtypes = [C.POINTER(akv_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
+                                                C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(st: int):
+    if st != AKV_OK:
+        raise AkvError(st, lib().akv_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: torch.Tensor | None) -> int | None:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t.data_ptr()
+
+
+def akv_version() -> int:
+    return lib().akv_version()
+
+
+def akv_layout_sizes(B: int, Hq: int, Hkv: int, D: int, Ncap: int) -> akv_sizes:
+    shp, out = akv_shape(B, Hq, Hkv, D, Ncap), akv_sizes()
+    _check(lib().akv_layout_sizes(C.byref(shp), C.byref(out)))
+    return out
+
+
+@dataclass
+class Cache:
+    """Caller-owned device buffers of one split-plane cache (torch owns the memory)."""
+    B: int
+    Hq: int
+    Hkv: int
+    D: int
+    Ncap: int
+    k_hi: torch.Tensor = field(repr=False, default=None)
+    k_mid: torch.Tensor = field(repr=False, default=None)
+    k_lo: torch.Tensor = field(repr=False, default=None)
+    v_hi: torch.Tensor = field(repr=False, default=None)
+    v_mid: torch.Tensor = field(repr=False, default=None)
+    v_lo: torch.Tensor = field(repr=False, default=None)
+    colmax: torch.Tensor = field(repr=False, default=None)
+    lens: torch.Tensor = field(repr=False, default=None)
+    flags: torch.Tensor = field(repr=False, default=None)
+    workspace: torch.Tensor = field(repr=False, default=None)
+    sizes: akv_sizes = field(repr=False, default=None)
+
+    @staticmethod
+    def allocate(B: int, Hq: int, Hkv: int, D: int, Ncap: int, device="cuda:0") -> "Cache":
+        sz = akv_layout_sizes(B, Hq, Hkv, D, Ncap)
+        u8 = lambda n: torch.empty(n, dtype=torch.uint8, device=device)
+        c = Cache(B, Hq, Hkv, D, Ncap, u8(sz.k_hi), u8(sz.k_mid), u8(sz.k_lo), u8(sz.v_hi), u8(sz.v_mid), u8(sz.v_lo),
+                  torch.empty(B * Hkv * D, dtype=torch.int16, device=device),
+                  torch.empty(B, dtype=torch.int32, device=device),
+                  torch.empty(AKV_NFLAGS, dtype=torch.int32, device=device), u8(sz.workspace), sz)
+        akv_cache_reset(c)
+        return c
+
+    def struct(self) -> akv_cache:
+        return akv_cache(akv_shape(self.B, self.Hq, self.Hkv, self.D, self.Ncap), _ptr(self.k_hi), _ptr(self.k_mid),
+                         _ptr(self.k_lo), _ptr(self.v_hi), _ptr(self.v_mid), _ptr(self.v_lo), _ptr(self.colmax),
+                         _ptr(self.lens), _ptr(self.flags))
+
+
+def akv_cache_reset(cache: Cache) -> None:
+    s = cache.struct()
+    _check(lib().akv_cache_reset(C.byref(s), _stream()))
+
+
+def akv_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, n_new: torch.Tensor | None = None) -> None:
+    """k_new, v_new: fp16 [B, Hkv, n, D] on the device; n_new: int32 [B] on the device or None."""
+    assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16
+    n = k_new.shape[2]
+    assert tuple(k_new.shape) == (cache.B, cache.Hkv, n, cache.D) == tuple(v_new.shape)
+    if n_new is not None:
+        assert n_new.dtype == torch.int32 and tuple(n_new.shape) == (cache.B,)
+    s = cache.struct()
+    _check(lib().akv_append(C.byref(s), _ptr(k_new), _ptr(v_new), _ptr(n_new), n, _stream()))
+
+
+def akv_unpack(cache: Cache) -> tuple[torch.Tensor, torch.Tensor]:
+    k = torch.empty(cache.B, cache.Hkv, cache.Ncap, cache.D, dtype=torch.float16, device=cache.k_hi.device)
+    v = torch.empty_like(k)
+    s = cache.struct()
+    _check(lib().akv_unpack(C.byref(s), _ptr(k), _ptr(v), _stream()))
+    return k, v
+
+
+@dataclass
+class DebugBuffers:
+    """Device tensors receiving the decisions of one akv_decode_attention call."""
+    lvlK: torch.Tensor
+    logits: torch.Tensor
+    a: torch.Tensor
+    sel: torch.Tensor
+    oest: torch.Tensor
+    Ehat: torch.Tensor
+    needV: torch.Tensor | None
+    appliedV: torch.Tensor
+
+    @staticmethod
+    def allocate(cache: Cache, topk: int = 32, want_needV: bool = True) -> "DebugBuffers":
+        dev = cache.k_hi.device
+        B, Hq, Hkv, D, N = cache.B, cache.Hq, cache.Hkv, cache.D, cache.Ncap
+        z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=dev)
+        return DebugBuffers(z((B, Hkv, D), torch.uint8), z((B, Hq, N), torch.float32), z((B, Hq, N), torch.int8),
+                            torch.full((B, Hq, topk), -1, dtype=torch.int32, device=dev), z((B, Hq, D), torch.float32),
+                            z((B, Hkv, D), torch.int16), z((B, Hkv, N, D), torch.uint8) if want_needV else None,
+                            z((B, Hkv, N), torch.uint8))
+
+    def struct(self) -> akv_debug:
+        return akv_debug(_ptr(self.lvlK), _ptr(self.logits), _ptr(self.a), _ptr(self.sel), _ptr(self.oest),
+                         _ptr(self.Ehat), _ptr(self.needV), _ptr(self.appliedV))
+
+
+def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None = None, *, scale: float = 0.0,
+                         topk: int = 32, guard_bits: int = 0, force_level: int = -1, max_len: int = 0,
+                         dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """q: fp16 [B, Hq, D] on the device; out: float32 or fp16 [B, Hq, D] (allocated if None)."""
+    assert q.dtype == torch.float16 and tuple(q.shape) == (cache.B, cache.Hq, cache.D)
+    if out is None:
+        out = torch.empty(cache.B, cache.Hq, cache.D, dtype=torch.float32, device=q.device)
+    assert out.dtype in (torch.float32, torch.float16) and tuple(out.shape) == tuple(q.shape)
+    ws = cache.workspace if workspace is None else workspace
+    d = dbg.struct() if dbg is not None else None
+    p = akv_params(scale, topk, guard_bits, force_level, 0 if out.dtype == torch.float32 else 1, max_len,
+                   C.pointer(d) if d is not None else None)
+    s = cache.struct()
+    _check(lib().akv_decode_attention(C.byref(s), _ptr(q), _ptr(out), C.byref(p), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def akv_fp16_decode_attention(k: torch.Tensor, v: torch.Tensor, lens: torch.Tensor, q: torch.Tensor,
+                              out: torch.Tensor | None = None, *, scale: float = 0.0, max_len: int = 0,
+                              workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """k, v: fp16 [B, Hkv, Ncap, D]; lens: int32 [B]; q: fp16 [B, Hq, D] -- all on the device."""
+    B, Hkv, Ncap, D = k.shape
+    Hq = q.shape[1]
+    assert k.dtype == v.dtype == q.dtype == torch.float16 and lens.dtype == torch.int32 and v.shape == k.shape
+    if out is None:
+        out = torch.empty(B, Hq, D, dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(akv_layout_sizes(B, Hq, Hkv, D, Ncap).fp16_workspace, dtype=torch.uint8, device=q.device)
+    shp = akv_shape(B, Hq, Hkv, D, Ncap)
+    _check(lib().akv_fp16_decode_attention(C.byref(shp), _ptr(k), _ptr(v), _ptr(lens), _ptr(q), _ptr(out), scale,
+                                           0 if out.dtype == torch.float32 else 1, max_len, _ptr(workspace),
+                                           workspace.numel(), _stream()))
+    return out

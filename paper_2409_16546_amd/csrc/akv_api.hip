@@ -1,0 +1,175 @@
+// C ABI of the library (declared in include/akv.h): argument checks, workspace carving, launches.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "akv_common.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+akv_status fail(akv_status st, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool shape_ok(const akv_shape& s)
+{
+    return s.B > 0 && s.Hq > 0 && s.Hkv > 0 && s.D == akv::kD && s.Hq % s.Hkv == 0 && s.Hq / s.Hkv <= akv::kMaxG &&
+           ((s.Hq / s.Hkv) & (s.Hq / s.Hkv - 1)) == 0 && s.Ncap > 0 && s.Ncap % AKV_TB == 0 &&
+           size_t(s.B) * s.Hq * size_t(s.Ncap) < (size_t(1) << 40);
+}
+
+akv_status check_cache(const akv_cache* c)
+{
+    if (!c) return fail(AKV_EINVAL, "cache is NULL");
+    if (!shape_ok(c->shape))
+        return fail(AKV_EINVAL, "bad shape: B=%d Hq=%d Hkv=%d D=%d Ncap=%d (need D=128, Hq/Hkv a power of two <= 8, Ncap %% 256 == 0)",
+                    c->shape.B, c->shape.Hq, c->shape.Hkv, c->shape.D, c->shape.Ncap);
+    if (!c->k_hi || !c->k_mid || !c->k_lo || !c->v_hi || !c->v_mid || !c->v_lo || !c->colmax || !c->lens || !c->flags)
+        return fail(AKV_EINVAL, "cache has a NULL plane / colmax / lens / flags pointer");
+    return AKV_OK;
+}
+
+akv_status hip_fail(hipError_t e, const char* what)
+{
+    return fail(AKV_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+int akv_version(void) { return 100; }
+
+const char* akv_last_error(void) { return g_err; }
+
+akv_status akv_layout_sizes(const akv_shape* shape, akv_sizes* out)
+{
+    if (!shape || !out) return fail(AKV_EINVAL, "NULL argument");
+    if (!shape_ok(*shape))
+        return fail(AKV_EINVAL, "bad shape: B=%d Hq=%d Hkv=%d D=%d Ncap=%d (need D=128, Hq/Hkv a power of two <= 8, Ncap %% 256 == 0)",
+                    shape->B, shape->Hq, shape->Hkv, shape->D, shape->Ncap);
+    const size_t e = size_t(shape->B) * shape->Hkv * size_t(shape->Ncap) * shape->D;   // elements of K (and of V)
+    out->k_hi = e; out->k_mid = e / 2; out->k_lo = e / 2;
+    out->v_hi = e; out->v_mid = e / 2; out->v_lo = e / 2;
+    out->colmax = size_t(shape->B) * shape->Hkv * shape->D * sizeof(uint16_t);
+    out->lens = size_t(shape->B) * sizeof(int32_t);
+    out->flags = AKV_NFLAGS * sizeof(int32_t);
+    out->workspace = akv::ws_layout(*shape).total;
+    out->fp16_workspace = akv::fp16_workspace_bytes(*shape);
+    return AKV_OK;
+}
+
+akv_status akv_cache_reset(const akv_cache* cache, void* stream)
+{
+    if (akv_status st = check_cache(cache)) return st;
+    akv_sizes sz;
+    akv_layout_sizes(&cache->shape, &sz);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    struct { void* p; size_t n; } bufs[] = {
+        {cache->k_hi, sz.k_hi}, {cache->k_mid, sz.k_mid}, {cache->k_lo, sz.k_lo}, {cache->v_hi, sz.v_hi},
+        {cache->v_mid, sz.v_mid}, {cache->v_lo, sz.v_lo}, {cache->colmax, sz.colmax}, {cache->lens, sz.lens},
+        {cache->flags, sz.flags}};
+    for (auto& bf : bufs) {
+        if (reinterpret_cast<uintptr_t>(bf.p) % 16) return fail(AKV_EINVAL, "cache buffers must be 16-byte aligned");
+        if (hipError_t e = akv::launch_zero(bf.p, bf.n, s)) return hip_fail(e, "zero launch");
+    }
+    return AKV_OK;
+}
+
+akv_status akv_append(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new,
+                      int32_t n, void* stream)
+{
+    if (akv_status st = check_cache(cache)) return st;
+    if (n < 0 || n > cache->shape.Ncap) return fail(AKV_EINVAL, "n = %d out of range 0..Ncap", n);
+    if (n > 0 && (!k_new || !v_new)) return fail(AKV_EINVAL, "k_new / v_new is NULL");
+    if (hipError_t e = akv::launch_append(*cache, k_new, v_new, n_new, n, static_cast<hipStream_t>(stream)))
+        return hip_fail(e, "append launch");
+    return AKV_OK;
+}
+
+akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, void* stream)
+{
+    if (akv_status st = check_cache(cache)) return st;
+    if (!k_out && !v_out) return AKV_OK;
+    if (hipError_t e = akv::launch_unpack(*cache, k_out, v_out, static_cast<hipStream_t>(stream)))
+        return hip_fail(e, "unpack launch");
+    return AKV_OK;
+}
+
+akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void* out, const akv_params* params,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (akv_status st = check_cache(cache)) return st;
+    if (!q || !out) return fail(AKV_EINVAL, "q / out is NULL");
+    akv_params p;
+    std::memset(&p, 0, sizeof p);
+    p.force_level = -1;
+    if (params) p = *params;
+    if (p.topk == 0) p.topk = 32;
+    if (p.topk < 1 || p.topk > AKV_MAX_TOPK) return fail(AKV_EINVAL, "topk = %d out of range 1..%d", p.topk, AKV_MAX_TOPK);
+    if (p.guard_bits < 0 || p.guard_bits > 12) return fail(AKV_EINVAL, "guard_bits = %d out of range 0..12", p.guard_bits);
+    if (p.force_level < -1 || p.force_level > 2) return fail(AKV_EINVAL, "force_level = %d out of range -1..2", p.force_level);
+    if (p.out_dtype != 0 && p.out_dtype != 1) return fail(AKV_EINVAL, "out_dtype = %d is neither 0 (f32) nor 1 (f16)", p.out_dtype);
+    if (p.max_len < 0 || p.max_len > cache->shape.Ncap) return fail(AKV_EINVAL, "max_len = %d out of range 0..Ncap", p.max_len);
+    if (!(p.scale == p.scale) || std::isinf(p.scale)) return fail(AKV_EINVAL, "scale is not finite");
+    const akv::WsLayout w = akv::ws_layout(cache->shape);
+    if (!workspace || workspace_bytes < w.total)
+        return fail(AKV_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, w.total);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(AKV_EWORKSPACE, "workspace is not 256-byte aligned");
+
+    akv::DecodeArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.s = cache->shape;
+    a.k_hi = cache->k_hi; a.k_mid = cache->k_mid; a.k_lo = cache->k_lo;
+    a.v_hi = cache->v_hi; a.v_mid = cache->v_mid; a.v_lo = cache->v_lo;
+    a.colmax = cache->colmax; a.lens = cache->lens; a.q = q; a.out = out;
+    const double scale = p.scale > 0.0f ? (double)p.scale : 1.0 / std::sqrt((double)a.s.D);
+    a.c = (float)(scale * 1.4426950408889634);
+    a.topk = p.topk; a.guard_bits = p.guard_bits; a.force_level = p.force_level; a.out_dtype = p.out_dtype;
+    a.max_len = p.max_len > 0 ? p.max_len : a.s.Ncap;
+    char* ws = static_cast<char*>(workspace);
+    a.logits = reinterpret_cast<float*>(ws + w.logits);
+    a.tilemax = reinterpret_cast<float*>(ws + w.tilemax);
+    a.M = reinterpret_cast<float*>(ws + w.M);
+    a.Ehat = reinterpret_cast<int32_t*>(ws + w.Ehat);
+    a.partO = reinterpret_cast<float*>(ws + w.partO);
+    a.partZ = reinterpret_cast<float*>(ws + w.partZ);
+    if (p.dbg) {
+        a.dbg = *p.dbg;
+        if (a.dbg.logits) a.logits = a.dbg.logits;   // same shape: the pass writes the export directly
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipError_t e = akv::launch_kpass(a, s)) return hip_fail(e, "K pass launch");
+    if (hipError_t e = akv::launch_mid(a, s)) return hip_fail(e, "mid step launch");
+    if (hipError_t e = akv::launch_vpass(a, s)) return hip_fail(e, "V pass launch");
+    return AKV_OK;
+}
+
+akv_status akv_fp16_decode_attention(const akv_shape* shape, const uint16_t* k, const uint16_t* v, const int32_t* lens,
+                                     const uint16_t* q, void* out, float scale, int32_t out_dtype, int32_t max_len,
+                                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!shape || !shape_ok(*shape)) return fail(AKV_EINVAL, "bad shape");
+    if (!k || !v || !lens || !q || !out) return fail(AKV_EINVAL, "NULL pointer argument");
+    if (out_dtype != 0 && out_dtype != 1) return fail(AKV_EINVAL, "out_dtype = %d is neither 0 (f32) nor 1 (f16)", out_dtype);
+    if (max_len < 0 || max_len > shape->Ncap) return fail(AKV_EINVAL, "max_len = %d out of range 0..Ncap", max_len);
+    const size_t need = akv::fp16_workspace_bytes(*shape);
+    if (!workspace || workspace_bytes < need)
+        return fail(AKV_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(AKV_EWORKSPACE, "workspace is not 256-byte aligned");
+    const float sc = scale > 0.0f ? scale : (float)(1.0 / std::sqrt((double)shape->D));
+    if (hipError_t e = akv::launch_fp16(*shape, k, v, lens, q, out, sc, out_dtype, max_len > 0 ? max_len : shape->Ncap,
+                                        workspace, static_cast<hipStream_t>(stream)))
+        return hip_fail(e, "fp16 attention launch");
+    return AKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Append tokens into the split-plane cache and its inverse.
+// "Dynamic Quantization": the cache keeps all 16 bits of every element, the first 8 / next 4 / last 4
+// bits in separately contiguous planes; "Quantization of K-Cache": K_colmax is kept while storing.
+#include "akv_common.h"
+
+namespace akv {
+
+// One workgroup per (sequence, KV head), 128 threads: thread d owns K channel d (so it is the only writer
+// of that column's nibble bytes and of colmax[d]); threads 0..63 own the V nibble byte of channels 2d, 2d+1.
+__global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t* __restrict__ k_new,
+                                                     const uint16_t* __restrict__ v_new,
+                                                     const int32_t* __restrict__ n_new, int n)
+{
+    const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+    const int Hkv = c.shape.Hkv, Ncap = c.shape.Ncap, NB = Ncap / kTB;
+    const int len = c.lens[b];
+    int cnt = n_new ? n_new[b] : n;
+    cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
+    if (len + cnt > Ncap) return;   // refused; the bump kernel counts it
+    const size_t bh = size_t(b) * Hkv + h;
+    const uint16_t* kn = k_new + bh * n * kD;
+    const uint16_t* vn = v_new + bh * n * kD;
+    uint32_t cm = c.colmax[bh * kD + d];
+    for (int i = 0; i < cnt; ++i) {
+        const int t = len + i, blk = t / kTB, j = t % kTB;
+        const uint32_t kx = kn[size_t(i) * kD + d];
+        const size_t col = (bh * NB + blk) * kD + d;
+        c.k_hi[col * kTB + j] = (uint8_t)(kx >> 8);
+        uint8_t* pm = c.k_mid + col * (kTB / 2) + j / 2;
+        uint8_t* pl = c.k_lo + col * (kTB / 2) + j / 2;
+        if (j & 1) {
+            *pm = (uint8_t)((*pm & 0x0F) | (((kx >> 4) & 15u) << 4));
+            *pl = (uint8_t)((*pl & 0x0F) | ((kx & 15u) << 4));
+        } else {
+            *pm = (uint8_t)((*pm & 0xF0) | ((kx >> 4) & 15u));
+            *pl = (uint8_t)((*pl & 0xF0) | (kx & 15u));
+        }
+        const uint32_t mag = kx & 0x7FFFu;   // |k| as bits: integer order is magnitude order
+        cm = mag > cm ? mag : cm;
+        const size_t row = bh * Ncap + t;
+        const uint32_t vx = vn[size_t(i) * kD + d];
+        c.v_hi[row * kD + d] = (uint8_t)(vx >> 8);
+        if (d < kD / 2) {
+            const uint32_t v0 = vn[size_t(i) * kD + 2 * d], v1 = vn[size_t(i) * kD + 2 * d + 1];
+            c.v_mid[row * (kD / 2) + d] = (uint8_t)(((v0 >> 4) & 15u) | (((v1 >> 4) & 15u) << 4));
+            c.v_lo[row * (kD / 2) + d] = (uint8_t)((v0 & 15u) | ((v1 & 15u) << 4));
+        }
+    }
+    c.colmax[bh * kD + d] = (uint16_t)cm;
+}
+
+// Runs after append_kernel on the same stream: lens += n_new, or count the refusal.
+__global__ void bump_lens_kernel(akv_cache c, const int32_t* __restrict__ n_new, int n)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= c.shape.B) return;
+    int cnt = n_new ? n_new[b] : n;
+    cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
+    const int len = c.lens[b];
+    if (len + cnt > c.shape.Ncap) atomicAdd(&c.flags[AKV_FLAG_OVERFLOW], 1);
+    else c.lens[b] = len + cnt;
+}
+
+hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
+                         hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(append_kernel, dim3(c.shape.Hkv, c.shape.B), dim3(128), 0, st, c, k_new, v_new, n_new, n);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(bump_lens_kernel, dim3((c.shape.B + 63) / 64), dim3(64), 0, st, c, n_new, n);
+    return hipGetLastError();
+}
+
+// planes -> fp16 [B][Hkv][Ncap][D]; one thread per (token, channel pair)
+__global__ __launch_bounds__(256) void unpack_kernel(akv_cache c, uint16_t* __restrict__ k_out,
+                                                     uint16_t* __restrict__ v_out)
+{
+    const int Hkv = c.shape.Hkv, Ncap = c.shape.Ncap, NB = Ncap / kTB;
+    const size_t idx = size_t(blockIdx.x) * 256 + threadIdx.x;          // over B*Hkv*Ncap*(D/2)
+    const size_t total = size_t(c.shape.B) * Hkv * Ncap * (kD / 2);
+    if (idx >= total) return;
+    const int dp = int(idx % (kD / 2));
+    const size_t row = idx / (kD / 2);                                   // (b*Hkv + h)*Ncap + t
+    const int t = int(row % Ncap);
+    const size_t bh = row / Ncap;
+    if (v_out) {
+        const uint32_t h0 = c.v_hi[row * kD + 2 * dp], h1 = c.v_hi[row * kD + 2 * dp + 1];
+        const uint32_t m = c.v_mid[row * (kD / 2) + dp], l = c.v_lo[row * (kD / 2) + dp];
+        v_out[row * kD + 2 * dp] = (uint16_t)((h0 << 8) | ((m & 15u) << 4) | (l & 15u));
+        v_out[row * kD + 2 * dp + 1] = (uint16_t)((h1 << 8) | ((m >> 4) << 4) | (l >> 4));
+    }
+    if (k_out) {
+        const int blk = t / kTB, j = t % kTB;
+        for (int u = 0; u < 2; ++u) {
+            const int d = 2 * dp + u;
+            const size_t col = (bh * NB + blk) * kD + d;
+            const uint32_t hi = c.k_hi[col * kTB + j];
+            const uint32_t m = c.k_mid[col * (kTB / 2) + j / 2], l = c.k_lo[col * (kTB / 2) + j / 2];
+            const uint32_t mn = (j & 1) ? (m >> 4) : (m & 15u), ln = (j & 1) ? (l >> 4) : (l & 15u);
+            k_out[row * kD + d] = (uint16_t)((hi << 8) | (mn << 4) | ln);
+        }
+    }
+}
+
+hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, hipStream_t st)
+{
+    const size_t total = size_t(c.shape.B) * c.shape.Hkv * c.shape.Ncap * (kD / 2);
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, c, k_out, v_out);
+    return hipGetLastError();
+}
+
+// zero a buffer with 16-byte stores (a kernel rather than a memset node, so that a caller may capture it)
+__global__ __launch_bounds__(256) void zero_kernel(uint4* __restrict__ p16, size_t n16, uint8_t* __restrict__ tail,
+                                                   int ntail)
+{
+    const size_t stride = size_t(gridDim.x) * 256;
+    for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride) p16[i] = make_uint4(0, 0, 0, 0);
+    if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return hipSuccess;
+    const size_t n16 = bytes / 16;   // buffers come from an allocator: 16-byte aligned
+    size_t blocks = (n16 + 255) / 256;
+    blocks = blocks < 1 ? 1 : (blocks > 8192 ? 8192 : blocks);
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<uint4*>(p), n16,
+                       reinterpret_cast<uint8_t*>(p) + n16 * 16, int(bytes - n16 * 16));
+    return hipGetLastError();
+}
+
+}  // namespace akv

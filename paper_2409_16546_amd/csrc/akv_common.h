@@ -1,0 +1,150 @@
+// Shared declarations of the AlignedKV HIP library (host launchers + device helpers).
+// Rules and layout: include/akv.h.  Paper sections are cited where an operation is defined.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/akv.h"
+
+namespace akv {
+
+constexpr int kD = 128;            // head dimension ("Runtime of AlignedKV": sqrt(128))
+constexpr int kTB = AKV_TB;        // tokens per K block
+constexpr int kAMin = -64;         // floor of the score exponent
+constexpr int kBuckets = 65;       // exponent buckets 0..64 of the approximate top-k
+constexpr int kMaxG = 8;           // query heads per KV head supported
+
+// K pass: one wave covers kKTile tokens (each lane kKTpl consecutive tokens of one block).
+constexpr int kKTpl = 8;
+constexpr int kKTile = 64 * kKTpl;                 // 512 tokens = 2 blocks
+constexpr int kKWaves = 4;                         // waves per workgroup
+constexpr int kKTokensPerWg = kKTile * kKWaves;    // 2048
+// V pass: one workgroup covers kVChunk tokens; a wave reads 8 token rows per step.
+constexpr int kVWaves = 4;
+constexpr int kVChunk = 512;
+
+// Offsets (bytes) into the decode workspace.
+struct WsLayout {
+    size_t logits;   // float [B][Hq][Ncap]
+    size_t tilemax;  // float [B][Hq][k_tiles(Ncap)]
+    size_t M;        // float [B][Hq]
+    size_t Ehat;     // int32 [B][Hkv][D]
+    size_t partO;    // float [B][Hq][v_splits(Ncap)][D]
+    size_t partZ;    // float [B][Hq][v_splits(Ncap)]
+    size_t total;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+inline __host__ __device__ int k_tiles(int ntok) { return (ntok + kKTile - 1) / kKTile; }      // K-pass tiles covering ntok
+inline __host__ __device__ int v_splits(int ntok) { return (ntok + kVChunk - 1) / kVChunk; }   // V-pass chunks covering ntok
+
+inline WsLayout ws_layout(const akv_shape& s)
+{
+    WsLayout w;
+    size_t off = 0;
+    const size_t bhq = size_t(s.B) * s.Hq;
+    w.logits = off;  off = align256(off + bhq * s.Ncap * sizeof(float));
+    w.tilemax = off; off = align256(off + bhq * k_tiles(s.Ncap) * sizeof(float));
+    w.M = off;       off = align256(off + bhq * sizeof(float));
+    w.Ehat = off;    off = align256(off + size_t(s.B) * s.Hkv * kD * sizeof(int32_t));
+    w.partO = off;   off = align256(off + bhq * v_splits(s.Ncap) * kD * sizeof(float));
+    w.partZ = off;   off = align256(off + bhq * v_splits(s.Ncap) * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+// Everything a decode kernel needs, passed by value.
+struct DecodeArgs {
+    akv_shape s;
+    const uint8_t *k_hi, *k_mid, *k_lo, *v_hi, *v_mid, *v_lo;
+    const uint16_t* colmax;
+    const int32_t* lens;
+    const uint16_t* q;
+    void* out;
+    float c;             // (float)(scale * log2(e))
+    int topk, guard_bits, force_level, out_dtype, max_len;
+    float* logits;       // [B][Hq][Ncap]
+    float* tilemax;
+    float* M;
+    int32_t* Ehat;
+    float* partO;
+    float* partZ;
+    akv_debug dbg;       // device pointers or NULL
+};
+
+// host launchers (defined next to their kernels)
+hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
+                         hipStream_t st);
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, hipStream_t st);
+hipError_t launch_kpass(const DecodeArgs& a, hipStream_t st);
+hipError_t launch_mid(const DecodeArgs& a, hipStream_t st);
+hipError_t launch_vpass(const DecodeArgs& a, hipStream_t st);
+hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v, const int32_t* lens, const uint16_t* q,
+                       void* out, float scale, int out_dtype, int max_len, void* ws, hipStream_t st);
+size_t fp16_workspace_bytes(const akv_shape& s);
+
+// ------------------------------------------------------------------ device helpers
+#if defined(__HIPCC__)
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);   // exact
+}
+__device__ __forceinline__ uint32_t float_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ int float_exp_field(float f) { return (int)((float_bits(f) >> 23) & 0xFFu); }
+
+// smallest level keeping at least m mantissa bits (2 / 6 / 10 kept at level 0 / 1 / 2)
+__device__ __forceinline__ int level_for_mantissa_bits(int m) { return m <= 2 ? 0 : (m <= 6 ? 1 : 2); }
+
+// Fill words for nibble planes that are not read ("Dynamic Quantization": the bits not read are 100...):
+// level 0: MID nibble = 8, LO nibble = 0;  level 1: MID read, LO nibble = 8.
+constexpr uint32_t kFill8 = 0x88888888u;
+
+// Assemble eight fp16 values from their planes.  H0, H1: the eight HI bytes (element i in byte i%4 of
+// H[i/4]); M, L: the eight MID / LO nibbles (element 2i in the low nibble of byte i).  Result: p[0] =
+// elements (0,2), p[1] = (1,3), p[2] = (4,6), p[3] = (5,7), first of the pair in the low half.
+__device__ __forceinline__ void assemble8(uint32_t H0, uint32_t H1, uint32_t M, uint32_t L, uint32_t (&p)[4])
+{
+    const uint32_t ev = ((M << 4) & 0xF0F0F0F0u) | (L & 0x0F0F0F0Fu);   // low bytes of elements 0,2,4,6
+    const uint32_t od = (M & 0xF0F0F0F0u) | ((L >> 4) & 0x0F0F0F0Fu);   // low bytes of elements 1,3,5,7
+    // v_perm_b32: result byte i = byte sel[i] of the pool {src0 (bytes 7..4), src1 (bytes 3..0)}
+    p[0] = __builtin_amdgcn_perm(H0, ev, 0x06010400u);
+    p[1] = __builtin_amdgcn_perm(H0, od, 0x07010500u);
+    p[2] = __builtin_amdgcn_perm(H1, ev, 0x06030402u);
+    p[3] = __builtin_amdgcn_perm(H1, od, 0x07030502u);
+}
+
+__device__ __forceinline__ float lo_half(uint32_t p) { return (float)__builtin_bit_cast(half2_t, p).x; }
+__device__ __forceinline__ float hi_half(uint32_t p) { return (float)__builtin_bit_cast(half2_t, p).y; }
+
+// Score exponent of a logit ("Quantization of V-Cache": the scores span many orders of magnitude):
+// x = (l - M) * c in two separately rounded fp32 operations, a = max(floor(x), -64).
+__device__ __forceinline__ float score_x(float l, float M, float c)
+{
+    const float diff = l - M;
+    return diff * c;            // the file is compiled with -ffp-contract=off: no fusion
+}
+__device__ __forceinline__ int score_a(float x)
+{
+    const float fl = floorf(x);
+    return fl < (float)kAMin ? kAMin : (int)fl;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ int wave_sum_int(int v)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+#endif  // __HIPCC__
+}  // namespace akv

@@ -1,0 +1,209 @@
+// V side of decode attention: Rule 2 per element, fetch per token row, softmax weights, O = S V~.
+// "Quantization of V-Cache": with O_est known, every addend s_t * v_td is aligned to the precision of the
+// result (Rule 2); the bit width of the addend is the bit width V is read at.
+#include "akv_common.h"
+
+namespace akv {
+
+// Byte-parallel form of Rule 2 for one token row.  With w_d = guard - 5 - Ehat_d and s = Ahat_t the
+// mantissa bits element (t,d) needs are m = ev' + w_d + s (ev' = max(exponent field, 1)); the row is read
+// at level >= 1 iff some m >= 3 and at level 2 iff some m >= 7.  Per byte: ev + B + (s + 64) with
+// B1_d = clamp(w_d + 61, 0, 128), B2_d = clamp(w_d + 57, 0, 128) sets bit 7 exactly when ev + w_d + s
+// reaches 3 resp. 7 (no carry: the sum is at most 31 + 128 + 64); the clamps only cut cases that are
+// decided for every ev in 0..31 and s in -64..0.  ev' differs from ev only for ev = 0, which adds the
+// row-independent test 1 + max_d w_d + s >= 3 (resp. 7).
+__device__ __forceinline__ uint32_t clamp_byte(int v) { return (uint32_t)(v < 0 ? 0 : (v > 128 ? 128 : v)); }
+
+template <int G, bool DEBUG>
+__global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
+{
+    __shared__ float red_s[kVWaves][G][kD + 1];
+
+    const int h = blockIdx.y, b = blockIdx.z, split = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane >> 3, cl = lane & 7;            // row within the wave's group of 8, channel slice 16*cl..16*cl+15
+    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
+    const int len = min(a.lens[b], Ncap);
+    const int c0 = split * kVChunk;
+    if (c0 >= len) return;                              // uniform
+    const size_t bh = size_t(b) * Hkv + h;
+    const int nsplit = v_splits(Ncap);
+
+    // ---- per-lane constants of Rule 2 for its 16 channels ----------------------------------------
+    uint32_t B1[4], B2[4];
+    int ehat[16];
+    int wmax = -100000;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        B1[i] = 0;
+        B2[i] = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int e = a.Ehat[bh * kD + cl * 16 + i * 4 + k];
+            ehat[i * 4 + k] = e;
+            const int w = a.guard_bits - 5 - e;
+            wmax = w > wmax ? w : wmax;
+            B1[i] |= clamp_byte(w + 61) << (8 * k);
+            B2[i] |= clamp_byte(w + 57) << (8 * k);
+        }
+    }
+    for (int o = 1; o < 8; o <<= 1) {
+        const int other = __shfl_xor(wmax, o);
+        wmax = other > wmax ? other : wmax;
+    }
+    float Mg[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) Mg[g] = a.M[size_t(b) * Hq + size_t(h) * G + g];
+
+    float acc[G][16], z[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        z[g] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
+    }
+
+    // ---- stream the chunk: 32 token rows per step per workgroup, 8 per wave ----------------------------
+    for (int it = 0; it < kVChunk / (8 * kVWaves); ++it) {
+        const int t = c0 + it * (8 * kVWaves) + wave * 8 + r;
+        const bool valid = t < len;
+        const size_t row = bh * Ncap + (valid ? t : 0);
+        uint4 hi = make_uint4(0, 0, 0, 0);
+        if (valid) hi = *reinterpret_cast<const uint4*>(a.v_hi + row * kD + cl * 16);
+        float p[G];
+        int ahat = kAMin;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float l = valid ? a.logits[(size_t(b) * Hq + size_t(h) * G + g) * Ncap + t] : Mg[g];
+            const float x = score_x(l, Mg[g], a.c);
+            const int ag = score_a(x);
+            ahat = ag > ahat ? ag : ahat;
+            p[g] = valid ? __builtin_amdgcn_exp2f(x) : 0.0f;
+        }
+        // row decision (Rule 2), byte-parallel over the lane's 16 channels
+        const uint32_t ssplat = (uint32_t)(ahat + 64) * 0x01010101u;
+        const uint32_t hw[4] = {hi.x, hi.y, hi.z, hi.w};
+        uint32_t any1 = 0, any2 = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t evp = (hw[i] >> 2) & 0x1F1F1F1Fu;
+            any1 |= evp + B1[i] + ssplat;
+            any2 |= evp + B2[i] + ssplat;
+        }
+        const uint64_t b1 = __ballot((any1 & 0x80808080u) != 0), b2 = __ballot((any2 & 0x80808080u) != 0);
+        const int sh = lane & 56;
+        const bool need1 = ((b1 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 3);
+        const bool need2 = ((b2 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 7);
+        int applied = need2 ? 2 : (need1 ? 1 : 0);
+        if (a.force_level >= 0) applied = a.force_level;
+
+        uint2 mid = make_uint2(kFill8, kFill8);                        // level 0: unread bits 1000 0000
+        uint2 lo = applied == 1 ? make_uint2(kFill8, kFill8) : make_uint2(0u, 0u);   // level 1: unread bits 1000
+        if (valid && applied >= 1) mid = *reinterpret_cast<const uint2*>(a.v_mid + row * (kD / 2) + cl * 8);
+        if (valid && applied >= 2) lo = *reinterpret_cast<const uint2*>(a.v_lo + row * (kD / 2) + cl * 8);
+
+        if (DEBUG && valid) {
+            if (a.dbg.appliedV && cl == 0) a.dbg.appliedV[bh * Ncap + t] = (uint8_t)applied;
+            if (a.dbg.needV) {
+                uint32_t nv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    nv[i] = 0;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        int ev = (int)((hw[i] >> (8 * k + 2)) & 31u);
+                        ev = ev < 1 ? 1 : ev;
+                        int need = level_for_mantissa_bits(10 + a.guard_bits - (ehat[i * 4 + k] - (ahat + ev - 15)));
+                        if (a.force_level >= 0) need = a.force_level;
+                        nv[i] |= (uint32_t)need << (8 * k);
+                    }
+                }
+                *reinterpret_cast<uint4*>(a.dbg.needV + (bh * Ncap + t) * kD + cl * 16) =
+                    make_uint4(nv[0], nv[1], nv[2], nv[3]);
+            }
+        }
+
+        uint32_t pa[4], pb[4];
+        assemble8(hi.x, hi.y, mid.x, lo.x, pa);   // channels 0..7 of the slice
+        assemble8(hi.z, hi.w, mid.y, lo.y, pb);   // channels 8..15
+        const float v[16] = {lo_half(pa[0]), lo_half(pa[1]), hi_half(pa[0]), hi_half(pa[1]),
+                             lo_half(pa[2]), lo_half(pa[3]), hi_half(pa[2]), hi_half(pa[3]),
+                             lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
+                             lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            z[g] += p[g];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(p[g], v[i], acc[g][i]);
+        }
+    }
+
+    // ---- reduce over the 8 rows of a wave, then over the waves ----------------------------------------
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        for (int o = 8; o < 64; o <<= 1) {
+            z[g] += __shfl_xor(z[g], o);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[g][i] += __shfl_xor(acc[g][i], o);
+        }
+        if (r == 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red_s[wave][g][cl * 16 + i] = acc[g][i];
+            if (cl == 0) red_s[wave][g][kD] = z[g];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * (kD + 1); idx += 64 * kVWaves) {
+        const int g = idx / (kD + 1), d = idx % (kD + 1);
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kVWaves; ++w) s += red_s[w][g][d];
+        const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
+        if (d < kD) a.partO[(hq * nsplit + split) * kD + d] = s;
+        else a.partZ[hq * nsplit + split] = s;
+    }
+}
+
+// out = sum_splits O / sum_splits Z  (every split uses the same global max, so no rescaling)
+__global__ __launch_bounds__(kD) void combine_kernel(DecodeArgs a)
+{
+    const int hq_i = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+    const int len = min(a.lens[b], a.s.Ncap);
+    const size_t hq = size_t(b) * a.s.Hq + hq_i;
+    const int nsplit = v_splits(a.s.Ncap), used = v_splits(len);
+    float o = 0.0f, zsum = 0.0f;
+    for (int s = 0; s < used; ++s) {
+        o += a.partO[(hq * nsplit + s) * kD + d];
+        zsum += a.partZ[hq * nsplit + s];
+    }
+    const float res = used > 0 ? o / zsum : 0.0f;
+    if (a.out_dtype == 0) reinterpret_cast<float*>(a.out)[hq * kD + d] = res;
+    else reinterpret_cast<_Float16*>(a.out)[hq * kD + d] = (_Float16)res;
+}
+
+template <int G>
+static void launch_vpass_g(const DecodeArgs& a, hipStream_t st)
+{
+    const dim3 grid(v_splits(a.max_len), a.s.Hkv, a.s.B), block(64 * kVWaves);
+    const bool debug = a.dbg.needV || a.dbg.appliedV;
+    if (debug) hipLaunchKernelGGL((vpass_kernel<G, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((vpass_kernel<G, false>), grid, block, 0, st, a);
+}
+
+hipError_t launch_vpass(const DecodeArgs& a, hipStream_t st)
+{
+    const int G = a.s.Hq / a.s.Hkv;
+    switch (G) {
+        case 1: launch_vpass_g<1>(a, st); break;
+        case 2: launch_vpass_g<2>(a, st); break;
+        case 4: launch_vpass_g<4>(a, st); break;
+        case 8: launch_vpass_g<8>(a, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(combine_kernel, dim3(a.s.Hq, a.s.B), dim3(kD), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace akv

@@ -1,0 +1,68 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/akv.h declares; host-only entry
+points (layout query, argument checks) behave as documented.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def A():
+    from paper_2409_16546_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2409_16546_amd import build
+        build.build_library(verbose=False)
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "akv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(akv_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_name_the_same_entry_points(A):
+    names = declared_functions()
+    assert names == sorted(A.EXPORTS)
+    L = A.lib()
+    for n in names:
+        assert getattr(L, n) is not None          # dlsym finds every declared symbol
+    assert A.akv_version() >= 100
+
+
+def test_layout_sizes_is_a_host_computation(A):
+    sz = A.akv_layout_sizes(8, 32, 32, 128, 4096)
+    e = 8 * 32 * 4096 * 128
+    assert (sz.k_hi, sz.k_mid, sz.k_lo, sz.v_hi, sz.v_mid, sz.v_lo) == (e, e // 2, e // 2, e, e // 2, e // 2)
+    assert sz.k_hi + sz.k_mid + sz.k_lo == 2 * e  # planes hold exactly the fp16 bytes: lossless, no padding
+    assert sz.colmax == 8 * 32 * 128 * 2 and sz.lens == 32 and sz.flags == 16
+    assert sz.workspace >= 8 * 32 * 4096 * 4 and sz.workspace % 256 == 0 and sz.fp16_workspace % 256 == 0
+
+
+@pytest.mark.parametrize("shape", [(0, 4, 4, 128, 256), (1, 4, 3, 128, 256), (1, 4, 4, 64, 256), (1, 4, 4, 128, 100),
+                                   (1, 32, 2, 128, 256), (1, 6, 2, 128, 256)])
+def test_bad_shapes_are_refused_with_a_message(A, shape):
+    with pytest.raises(A.AkvError) as e:
+        A.akv_layout_sizes(*shape)
+    assert e.value.status == A.AKV_EINVAL and "bad shape" in str(e.value)
+
+
+def test_struct_layouts_match_the_header(A):
+    # the binding's ctypes structs mirror the C structs field for field
+    text = open(os.path.join(ROOT, "include", "akv.h")).read()
+    for struct, cls in (("akv_shape", A.akv_shape), ("akv_sizes", A.akv_sizes), ("akv_cache", A.akv_cache),
+                        ("akv_debug", A.akv_debug), ("akv_params", A.akv_params)):
+        body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (struct, struct), text, flags=re.S).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        fields = []
+        for decl in body.split(";"):
+            decl = decl.strip()
+            if not decl:
+                continue
+            names = decl.replace("*", " ").split(",")
+            first = names[0].split()[-1]
+            fields += [first] + [n.strip() for n in names[1:]]
+        assert fields == [f[0] for f in cls._fields_], struct

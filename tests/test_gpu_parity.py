@@ -1,0 +1,225 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+Cache bytes, K levels, logits, score exponents, top-k, O_est, result exponents and V masks are compared
+bit for bit; the attention output within max-abs 2e-3 and rel-L2 1e-3."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def T():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from oracle import akv_oracle
+    akv_oracle.build()
+    import akv_testlib
+    return akv_testlib
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------------ append / unpack
+
+def test_append_bulk_matches_oracle_bytes_and_unpack_is_lossless(T):
+    from paper_2409_16546_amd import workloads, binding as A
+    say("append: edge bit patterns B2 Hkv3 N700 Ncap768, ragged")
+    k, v = workloads.edge_patterns(2, 3, 700)
+    lens = [700, 389]
+    oc = T.oracle_cache(k, v, lens, 768)
+    gc = T.gpu_cache(k, v, lens, 3, 768)
+    torch.cuda.synchronize()
+    T.assert_cache_equal(gc, oc)
+    ku, vu = A.akv_unpack(gc)
+    kb, vb = T.bits(ku), T.bits(vu)
+    for b, n in enumerate(lens):
+        assert np.array_equal(kb[b, :, :n], T.bits(k)[b, :, :n]) and np.array_equal(vb[b, :, :n], T.bits(v)[b, :, :n])
+        assert not kb[b, :, n:].any() and not vb[b, :, n:].any()
+
+
+def test_append_token_by_token_and_capacity_flag(T):
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    say("append: token by token, ragged counts, overflow refusal")
+    B, Hkv, D, Ncap = 3, 2, 128, 256
+    k, v = workloads.edge_patterns(B, Hkv, 300, seed=11)
+    oc = O.Cache.empty(B, Hkv, D, Ncap)
+    gc = A.Cache.allocate(B, 2, Hkv, D, Ncap, DEV)
+    pos = 0
+    rng = np.random.default_rng(5)
+    for step, n in enumerate([1, 1, 1, 2, 5, 1, 64, 1, 130, 1, 1]):
+        n_new = rng.integers(0, n + 1, size=B).astype(np.int32) if step % 3 == 2 else np.full(B, n, np.int32)
+        kn, vn = k[:, :, pos:pos + n].contiguous(), v[:, :, pos:pos + n].contiguous()
+        O.append(oc, T.bits(kn), T.bits(vn), n_new)
+        A.akv_append(gc, kn.to(DEV), vn.to(DEV), torch.from_numpy(n_new).to(DEV))
+        pos += n
+    torch.cuda.synchronize()
+    T.assert_cache_equal(gc, oc)
+    assert int(gc.flags.cpu()[0]) == 0
+    # an append that does not fit leaves the sequence unchanged and raises the flag
+    kn, vn = k[:, :, :200].contiguous(), v[:, :, :200].contiguous()
+    n_new = np.array([200, 1, 0], np.int32)
+    refused = O.append(oc, T.bits(kn), T.bits(vn), n_new)
+    A.akv_append(gc, kn.to(DEV), vn.to(DEV), torch.from_numpy(n_new).to(DEV))
+    torch.cuda.synchronize()
+    assert refused >= 1 and int(gc.flags.cpu()[0]) == refused
+    T.assert_cache_equal(gc, oc)
+
+
+# ------------------------------------------------------------------------------------------ decode parity
+
+CASES = [
+    # name, cfg, overrides, lens (None = full), params
+    ("cfg1-small", 1, dict(B=1, Hq=4, Hkv=4, N=1024), None, {}),
+    ("cfg2-ragged", 2, dict(B=3, Hq=4, Hkv=4, N=1500), [1500, 1237, 513], {}),
+    ("cfg2-guard2", 2, dict(B=2, Hq=2, Hkv=2, N=1100), [1100, 777], dict(guard_bits=2)),
+    ("cfg3-token-outliers", 3, dict(B=2, Hq=4, Hkv=4, N=2304), [2304, 2303], {}),
+    ("cfg4-gqa4", 4, dict(B=2, Hq=8, Hkv=2, N=2600), [2600, 1999], {}),
+    ("cfg4-gqa2-topk8", 4, dict(B=1, Hq=4, Hkv=2, N=900), None, dict(topk=8)),
+    ("cfg4-gqa8", 4, dict(B=1, Hq=8, Hkv=1, N=700), None, {}),
+    ("cfg5-student-t", 5, dict(B=3, Hq=8, Hkv=2, N=3000), None, {}),
+    ("cfg1-force0", 1, dict(B=1, Hq=2, Hkv=2, N=600), None, dict(force_level=0)),
+    ("cfg1-force1", 1, dict(B=1, Hq=2, Hkv=2, N=600), None, dict(force_level=1)),
+    ("cfg1-force2-control", 1, dict(B=1, Hq=2, Hkv=2, N=600), None, dict(force_level=2)),
+    ("cfg2-scale", 2, dict(B=1, Hq=2, Hkv=2, N=520), None, dict(scale=0.05)),
+]
+
+
+@pytest.mark.parametrize("name,cfg,over,lens,params", CASES, ids=[c[0] for c in CASES])
+def test_decode_matches_oracle(T, name, cfg, over, lens, params):
+    from paper_2409_16546_amd import workloads
+    say(f"decode parity: {name} cfg={cfg} {over} lens={lens} params={params}")
+    w = workloads.make(cfg, **over)
+    lens = w.lens.tolist() if lens is None else lens
+    gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, **params)
+    T.assert_cache_equal(gc, oc)
+    err, rl2 = T.assert_decode_equal(out, dbg, r, lens, w.Hq // w.Hkv, name)
+    say(f"  max-abs {err:.2e} rel-L2 {rl2:.2e} levels K {np.bincount(r.lvlK.ravel(), minlength=3)} "
+        f"V rows {r.counts[3:6] // 128}")
+
+
+def test_decode_edge_lengths_empty_one_and_smallest_capacity(T):
+    from paper_2409_16546_amd import workloads
+    say("decode parity: lens 0 / 1 / 255 / 256, Ncap 256")
+    w = workloads.make(2, B=4, Hq=4, Hkv=2, N=256)
+    lens = [0, 1, 255, 256]
+    gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, Ncap=256)
+    T.assert_decode_equal(out, dbg, r, lens, 2, "edge-lens")
+
+
+def test_decode_raw_bit_patterns_with_zeros_and_subnormals(T):
+    from paper_2409_16546_amd import workloads
+    say("decode parity: K, V of random finite bit patterns (zeros, subnormals, 65504)")
+    k, v = workloads.edge_patterns(1, 2, 640, seed=3)
+    k = (k.float() * 2.0 ** -12).to(torch.float16)     # keep logits finite in fp32 and fp16 ranges sane
+    v = (v.float().clamp(-100, 100)).to(torch.float16)
+    q = workloads.make(1, B=1, Hq=2, Hkv=2, N=256).q
+    lens = [640]
+    gc, oc, out, dbg, r = T.run_both(k, v, q, lens)
+    T.assert_cache_equal(gc, oc)
+    T.assert_decode_equal(out, dbg, r, lens, 1, "raw-bits")
+
+
+def test_decode_is_deterministic_and_fp16_output(T):
+    from paper_2409_16546_amd import workloads, binding as A
+    say("decode: run twice, bitwise equal; fp16 output = rounded fp32 output")
+    w = workloads.make(2, B=2, Hq=4, Hkv=4, N=1024)
+    gc = T.gpu_cache(w.k, w.v, w.lens.tolist(), w.Hq, 1024)
+    q = w.q.to(DEV)
+    o1 = A.akv_decode_attention(gc, q).clone()
+    o2 = A.akv_decode_attention(gc, q).clone()
+    o16 = A.akv_decode_attention(gc, q, out=torch.empty_like(q))
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    assert torch.equal(o16, o1.to(torch.float16))
+
+
+def test_max_len_hint_gives_the_same_result(T):
+    from paper_2409_16546_amd import workloads, binding as A
+    say("decode: max_len hint bounds the launch, same result")
+    w = workloads.make(2, B=2, Hq=2, Hkv=2, N=700)
+    gc = T.gpu_cache(w.k, w.v, [700, 300], w.Hq, 4096)
+    q = w.q.to(DEV)
+    o1 = A.akv_decode_attention(gc, q).clone()
+    o2 = A.akv_decode_attention(gc, q, max_len=700).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+
+
+def test_bad_arguments_are_refused_on_the_host(T):
+    from paper_2409_16546_amd import binding as A
+    say("errors: bad shape / params / workspace -> status codes, nothing launched")
+    with pytest.raises(A.AkvError) as e:
+        A.akv_layout_sizes(1, 4, 4, 64, 256)
+    assert e.value.status == A.AKV_EINVAL
+    with pytest.raises(A.AkvError):
+        A.akv_layout_sizes(1, 4, 4, 128, 300)
+    gc = A.Cache.allocate(1, 2, 2, 128, 256, DEV)
+    q = torch.zeros(1, 2, 128, dtype=torch.float16, device=DEV)
+    for bad in (dict(topk=65), dict(guard_bits=13), dict(force_level=3), dict(max_len=257)):
+        with pytest.raises(A.AkvError) as e:
+            A.akv_decode_attention(gc, q, **bad)
+        assert e.value.status == A.AKV_EINVAL
+    with pytest.raises(A.AkvError) as e:
+        A.akv_decode_attention(gc, q, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.status == A.AKV_EWORKSPACE
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------ fp16 yardstick
+
+@pytest.mark.parametrize("G", [1, 4])
+def test_fp16_yardstick_matches_textbook_attention(T, G):
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    say(f"fp16 yardstick: G={G} ragged, against fp64 textbook attention")
+    w = workloads.make(2, B=3, Hq=2 * G, Hkv=2, N=1300)
+    lens = np.array([1300, 511, 0], np.int32)
+    Ncap = 1536
+    kp = torch.zeros(3, 2, Ncap, 128, dtype=torch.float16)
+    vp = torch.zeros_like(kp)
+    kp[:, :, :1300], vp[:, :, :1300] = w.k, w.v
+    out = A.akv_fp16_decode_attention(kp.to(DEV), vp.to(DEV), torch.from_numpy(lens).to(DEV), w.q.to(DEV))
+    torch.cuda.synchronize()
+    ref = O.fp16_attention(T.bits(kp), T.bits(vp), lens, T.bits(w.q))
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() <= T.MAX_ABS and T.rel_l2(got, ref) <= T.REL_L2
+    assert not got[2].any()
+
+
+# ------------------------------------------------------------------------------------------ full bench size, sampled
+
+def test_cfg2_full_size_sampled_against_oracle(T):
+    """BASELINE config 2 at full size in the launch configuration bench.py times (max_len = N, no debug
+    exports in the timed call); 6 sampled (sequence, head) pairs are recomputed by the oracle."""
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    say("full size: cfg2 B8 H32/32 N4096, 6 sampled (b, h) pairs")
+    w = workloads.make(2)
+    N = 4096
+    gc = T.gpu_cache(w.k, w.v, w.lens.tolist(), w.Hq, N)
+    q = w.q.to(DEV)
+    out_plain = A.akv_decode_attention(gc, q, max_len=N).clone()       # the benchmarked launch
+    dbg = A.DebugBuffers.allocate(gc)
+    out_dbg = A.akv_decode_attention(gc, q, max_len=N, dbg=dbg)
+    torch.cuda.synchronize()
+    assert torch.equal(out_plain, out_dbg)                              # exports do not change the result
+    rng = np.random.default_rng(0)
+    for b, h in zip(rng.integers(0, 8, 6), rng.integers(0, 32, 6)):
+        b, h = int(b), int(h)
+        oc = T.oracle_cache(w.k[b:b + 1, h:h + 1], w.v[b:b + 1, h:h + 1], [N], N)
+        r = O.decode_attention(oc, T.bits(w.q[b:b + 1, h:h + 1]))
+        sub = A.DebugBuffers(dbg.lvlK[b:b + 1, h:h + 1], dbg.logits[b:b + 1, h:h + 1], dbg.a[b:b + 1, h:h + 1],
+                             dbg.sel[b:b + 1, h:h + 1], dbg.oest[b:b + 1, h:h + 1], dbg.Ehat[b:b + 1, h:h + 1],
+                             dbg.needV[b:b + 1, h:h + 1], dbg.appliedV[b:b + 1, h:h + 1])
+        sub = A.DebugBuffers(*[x.contiguous() if x is not None else None for x in
+                               (sub.lvlK, sub.logits, sub.a, sub.sel, sub.oest, sub.Ehat, sub.needV, sub.appliedV)])
+        err, rl2 = T.assert_decode_equal(out_plain[b:b + 1, h:h + 1], sub, r, [N], 1, f"cfg2 b={b} h={h}")
+        say(f"  b={b} h={h}: max-abs {err:.2e} rel-L2 {rl2:.2e}")

@@ -116,6 +116,9 @@ typedef struct akv_params {
     int32_t out_dtype;    /* 0: out is float32 [B][Hq][D]; 1: out is fp16 [B][Hq][D]                 */
     int32_t max_len;      /* host-known upper bound of lens[] used to size the launch; 0 means Ncap  */
     const akv_debug *dbg; /* host pointer to a struct of device pointers, or NULL                    */
+    void *const *events;  /* host pointer to 4 hipEvent_t, or NULL: the library records them on the
+                             stream before the K pass, after it, after the mid step and after the V
+                             pass + combine, so that a caller can time each kernel in place         */
 } akv_params;
 
 #define AKV_MAX_TOPK 64

@@ -49,7 +49,8 @@ class akv_debug(C.Structure):
 
 class akv_params(C.Structure):
     _fields_ = [("scale", C.c_float), ("topk", C.c_int32), ("guard_bits", C.c_int32), ("force_level", C.c_int32),
-                ("out_dtype", C.c_int32), ("max_len", C.c_int32), ("dbg", C.POINTER(akv_debug))]
+                ("out_dtype", C.c_int32), ("max_len", C.c_int32), ("dbg", C.POINTER(akv_debug)),
+                ("events", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -129,6 +130,7 @@ class Cache:
     flags: torch.Tensor = field(repr=False, default=None)
     workspace: torch.Tensor = field(repr=False, default=None)
     sizes: akv_sizes = field(repr=False, default=None)
+    _struct: akv_cache = field(repr=False, default=None)
 
     @staticmethod
     def allocate(B: int, Hq: int, Hkv: int, D: int, Ncap: int, device="cuda:0") -> "Cache":
@@ -142,9 +144,11 @@ class Cache:
         return c
 
     def struct(self) -> akv_cache:
-        return akv_cache(akv_shape(self.B, self.Hq, self.Hkv, self.D, self.Ncap), _ptr(self.k_hi), _ptr(self.k_mid),
-                         _ptr(self.k_lo), _ptr(self.v_hi), _ptr(self.v_mid), _ptr(self.v_lo), _ptr(self.colmax),
-                         _ptr(self.lens), _ptr(self.flags))
+        if self._struct is None:   # the tensors never change after allocation
+            self._struct = akv_cache(akv_shape(self.B, self.Hq, self.Hkv, self.D, self.Ncap), _ptr(self.k_hi),
+                                     _ptr(self.k_mid), _ptr(self.k_lo), _ptr(self.v_hi), _ptr(self.v_mid),
+                                     _ptr(self.v_lo), _ptr(self.colmax), _ptr(self.lens), _ptr(self.flags))
+        return self._struct
 
 
 def akv_cache_reset(cache: Cache) -> None:
@@ -200,8 +204,10 @@ class DebugBuffers:
 
 def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None = None, *, scale: float = 0.0,
                          topk: int = 32, guard_bits: int = 0, force_level: int = -1, max_len: int = 0,
-                         dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
-    """q: fp16 [B, Hq, D] on the device; out: float32 or fp16 [B, Hq, D] (allocated if None)."""
+                         dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None,
+                         events=None) -> torch.Tensor:
+    """q: fp16 [B, Hq, D] on the device; out: float32 or fp16 [B, Hq, D] (allocated if None).
+    events: None or a ctypes array of 4 hipEvent_t handles the library records between its kernels."""
     assert q.dtype == torch.float16 and tuple(q.shape) == (cache.B, cache.Hq, cache.D)
     if out is None:
         out = torch.empty(cache.B, cache.Hq, cache.D, dtype=torch.float32, device=q.device)
@@ -209,7 +215,7 @@ def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None
     ws = cache.workspace if workspace is None else workspace
     d = dbg.struct() if dbg is not None else None
     p = akv_params(scale, topk, guard_bits, force_level, 0 if out.dtype == torch.float32 else 1, max_len,
-                   C.pointer(d) if d is not None else None)
+                   C.pointer(d) if d is not None else None, events)
     s = cache.struct()
     _check(lib().akv_decode_attention(C.byref(s), _ptr(q), _ptr(out), C.byref(p), _ptr(ws), ws.numel(), _stream()))
     return out

@@ -147,9 +147,16 @@ akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void*
         if (a.dbg.logits) a.logits = a.dbg.logits;   // same shape: the pass writes the export directly
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    auto mark = [&](int i) -> hipError_t {
+        return p.events ? hipEventRecord(static_cast<hipEvent_t>(p.events[i]), s) : hipSuccess;
+    };
+    if (hipError_t e = mark(0)) return hip_fail(e, "hipEventRecord");
     if (hipError_t e = akv::launch_kpass(a, s)) return hip_fail(e, "K pass launch");
+    if (hipError_t e = mark(1)) return hip_fail(e, "hipEventRecord");
     if (hipError_t e = akv::launch_mid(a, s)) return hip_fail(e, "mid step launch");
+    if (hipError_t e = mark(2)) return hip_fail(e, "hipEventRecord");
     if (hipError_t e = akv::launch_vpass(a, s)) return hip_fail(e, "V pass launch");
+    if (hipError_t e = mark(3)) return hip_fail(e, "hipEventRecord");
     return AKV_OK;
 }
 

@@ -22,7 +22,7 @@ akv_status fail(akv_status st, const char* fmt, ...)
 bool shape_ok(const akv_shape& s)
 {
     return s.B > 0 && s.Hq > 0 && s.Hkv > 0 && s.D == akv::kD && s.Hq % s.Hkv == 0 && s.Hq / s.Hkv <= akv::kMaxG &&
-           ((s.Hq / s.Hkv) & (s.Hq / s.Hkv - 1)) == 0 && s.Ncap > 0 && s.Ncap % AKV_TB == 0 &&
+           ((s.Hq / s.Hkv) & (s.Hq / s.Hkv - 1)) == 0 && s.Ncap > 0 && s.Ncap % AKV_TB == 0 && s.Ncap <= (1 << 22) &&
            size_t(s.B) * s.Hq * size_t(s.Ncap) < (size_t(1) << 40);
 }
 

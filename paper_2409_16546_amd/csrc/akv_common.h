@@ -119,6 +119,43 @@ __device__ __forceinline__ void assemble8(uint32_t H0, uint32_t H1, uint32_t M, 
     p[3] = __builtin_amdgcn_perm(H1, od, 0x07030502u);
 }
 
+// Raw buffer loads (the hardware range check makes predication free): a load whose byte offset is at or
+// beyond the buffer's size returns zero and fetches nothing, so "do not read this plane" is an offset of
+// kSkip instead of a branch, and every load of a loop can be issued unconditionally and early.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+constexpr uint32_t kSkip = 0x80000000u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // raw, 32-bit format
+}
+__device__ __forceinline__ uint32_t buf_load_b32(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+}
+__device__ __forceinline__ u32x2_t buf_load_b64(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+}
+__device__ __forceinline__ u32x4_t buf_load_b128(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+}
+
+// Variant of assemble8 taking the fill for unread bits as a per-byte constant OR-ed into the low bytes:
+// level 0 -> 0x80808080 (with M = L = 0), level 1 -> 0x08080808 (with L = 0), level 2 -> 0.
+__device__ __forceinline__ void assemble8_fill(uint32_t H0, uint32_t H1, uint32_t M, uint32_t L, uint32_t fill,
+                                               uint32_t (&p)[4])
+{
+    const uint32_t ev = ((M << 4) & 0xF0F0F0F0u) | (L & 0x0F0F0F0Fu) | fill;
+    const uint32_t od = (M & 0xF0F0F0F0u) | ((L >> 4) & 0x0F0F0F0Fu) | fill;
+    p[0] = __builtin_amdgcn_perm(H0, ev, 0x06010400u);
+    p[1] = __builtin_amdgcn_perm(H0, od, 0x07010500u);
+    p[2] = __builtin_amdgcn_perm(H1, ev, 0x06030402u);
+    p[3] = __builtin_amdgcn_perm(H1, od, 0x07030502u);
+}
+__device__ __forceinline__ uint32_t fill_for_level(int lv) { return lv == 0 ? 0x80808080u : (lv == 1 ? 0x08080808u : 0u); }
+
 __device__ __forceinline__ float lo_half(uint32_t p) { return (float)__builtin_bit_cast(half2_t, p).x; }
 __device__ __forceinline__ float hi_half(uint32_t p) { return (float)__builtin_bit_cast(half2_t, p).y; }
 

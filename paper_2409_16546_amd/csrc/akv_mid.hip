@@ -9,14 +9,19 @@ namespace akv {
 constexpr int kMidThreads = 256;
 
 // One workgroup per (sequence, KV head); the G query heads of the group are handled one after another.
+// Logits are walked 1024 at a time (a float4 per thread); the selected V rows are fetched by all threads at
+// once into LDS so that O_est costs one memory latency, then each channel runs its ordered FMA chain.
 template <int G>
 __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
 {
+    constexpr int kWaves = kMidThreads / 64;
+    constexpr int kChunk = kMidThreads * 4;
     __shared__ int cnt_s[kBuckets];
-    __shared__ float redf_s[kMidThreads / 64];
-    __shared__ int wlt_s[kMidThreads / 64], weq_s[kMidThreads / 64];
+    __shared__ float redf_s[kWaves];
+    __shared__ int wlt_s[kWaves], weq_s[kWaves];
     __shared__ int sel_s[AKV_MAX_TOPK];
     __shared__ float phat_s[AKV_MAX_TOPK];
+    __shared__ uint16_t v_s[AKV_MAX_TOPK][kD];
     __shared__ int J_s, fromcut_s;
 
     const int h = blockIdx.x, b = blockIdx.y;
@@ -42,13 +47,20 @@ __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
         if (lane == 0) redf_s[wave] = m;
         __syncthreads();
         float M = redf_s[0];
-        for (int w = 1; w < kMidThreads / 64; ++w) M = fmaxf(M, redf_s[w]);
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, redf_s[w]);
 
         // ---- histogram of score exponents: bucket j = -a_t, 0..64 -------------------------------------
-        for (int t = tid; t < len; t += kMidThreads) {
-            const int at = score_a(score_x(lg[t], M, a.c));
-            atomicAdd(&cnt_s[-at], 1);
-            if (a.dbg.a) a.dbg.a[hq * Ncap + t] = (int8_t)at;
+        for (int t0 = tid * 4; t0 < len; t0 += kChunk) {
+            const float4 l4 = *reinterpret_cast<const float4*>(lg + t0);   // Ncap % 256 == 0: the vector stays inside the row
+            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (t0 + i < len) {
+                    const int at = score_a(score_x(lv[i], M, a.c));
+                    atomicAdd(&cnt_s[-at], 1);
+                    if (a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)at;
+                }
+            }
         }
         __syncthreads();
         const int kk = a.topk < len ? a.topk : len;
@@ -63,25 +75,44 @@ __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
 
         // ---- ordered selection: every token above the cut bucket, the first `fromcut` of the cut bucket --
         int tot_lt = 0, tot_eq = 0;   // tokens of each kind before the current chunk (same in all threads)
-        for (int c0 = 0; c0 < len; c0 += kMidThreads) {
-            const int t = c0 + tid;
-            float x = 0.0f;
-            int j = 1000;
-            if (t < len) {
-                x = score_x(lg[t], M, a.c);
-                j = -score_a(x);
+        for (int c0 = 0; c0 < len; c0 += kChunk) {
+            const int t0 = c0 + tid * 4;
+            float x[4];
+            int j[4];
+            int c_lt = 0, c_eq = 0;
+            if (t0 < len) {
+                const float4 l4 = *reinterpret_cast<const float4*>(lg + t0);
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    x[i] = score_x(lv[i], M, a.c);
+                    j[i] = t0 + i < len ? -score_a(x[i]) : 1000;
+                    c_lt += j[i] < J;
+                    c_eq += j[i] == J;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    x[i] = 0.0f;
+                    j[i] = 1000;
+                }
             }
-            const bool is_lt = j < J, is_eq = j == J;
-            const uint64_t blt = __ballot(is_lt), beq = __ballot(is_eq);
-            const uint64_t below_me = (uint64_t(1) << lane) - 1;
-            if (lane == 0) {
-                wlt_s[wave] = __popcll(blt);
-                weq_s[wave] = __popcll(beq);
+            int s_lt = c_lt, s_eq = c_eq;   // inclusive scan over the lanes of the wave
+            for (int o = 1; o < 64; o <<= 1) {
+                const int u_lt = __shfl_up(s_lt, o), u_eq = __shfl_up(s_eq, o);
+                if (lane >= o) {
+                    s_lt += u_lt;
+                    s_eq += u_eq;
+                }
+            }
+            if (lane == 63) {
+                wlt_s[wave] = s_lt;
+                weq_s[wave] = s_eq;
             }
             __syncthreads();
-            int n_lt = tot_lt + __popcll(blt & below_me), n_eq = tot_eq + __popcll(beq & below_me);
+            int n_lt = tot_lt + s_lt - c_lt, n_eq = tot_eq + s_eq - c_eq;   // tokens of each kind before this thread's four
             int chunk_lt = 0, chunk_eq = 0;
-            for (int w = 0; w < kMidThreads / 64; ++w) {
+            for (int w = 0; w < kWaves; ++w) {
                 if (w < wave) {
                     n_lt += wlt_s[w];
                     n_eq += weq_s[w];
@@ -89,12 +120,18 @@ __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
                 chunk_lt += wlt_s[w];
                 chunk_eq += weq_s[w];
             }
-            if (is_lt || (is_eq && n_eq < fromcut)) {
-                const int pos = n_lt + (n_eq < fromcut ? n_eq : fromcut);
-                const float fl = floorf(x);
-                const float f = x - fl;
-                sel_s[pos] = t;
-                phat_s[pos] = ldexpf(1.0f + f, -j);   // piecewise-linear 2^x with the exponent floored at -64
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool is_lt = j[i] < J, is_eq = j[i] == J;
+                if (is_lt || (is_eq && n_eq < fromcut)) {
+                    const int pos = n_lt + (n_eq < fromcut ? n_eq : fromcut);
+                    const float fl = floorf(x[i]);
+                    const float f = x[i] - fl;
+                    sel_s[pos] = t0 + i;
+                    phat_s[pos] = ldexpf(1.0f + f, -j[i]);   // piecewise-linear 2^x with the exponent floored at -64
+                }
+                n_lt += is_lt;
+                n_eq += is_eq;
             }
             tot_lt += chunk_lt;
             tot_eq += chunk_eq;
@@ -103,17 +140,35 @@ __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
         }
         __syncthreads();
 
-        // ---- O_est over the selected rows at full 16 bits, result exponents --------------------------
+        // ---- the selected rows at full 16 bits -> LDS (8 threads per row, all rows in flight together) ----
+        for (int row = tid >> 3; row < kk; row += kMidThreads / 8) {
+            const int cl = tid & 7;
+            const size_t vrow = bh * Ncap + sel_s[row];
+            const uint4 hi = *reinterpret_cast<const uint4*>(a.v_hi + vrow * kD + cl * 16);
+            const uint2 mid = *reinterpret_cast<const uint2*>(a.v_mid + vrow * (kD / 2) + cl * 8);
+            const uint2 lo = *reinterpret_cast<const uint2*>(a.v_lo + vrow * (kD / 2) + cl * 8);
+            uint32_t pa[4], pb[4];
+            assemble8(hi.x, hi.y, mid.x, lo.x, pa);
+            assemble8(hi.z, hi.w, mid.y, lo.y, pb);
+            uint16_t* dst = &v_s[row][cl * 16];
+            const uint32_t pp[8] = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], pb[2], pb[3]};
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {   // pairs (0,2),(1,3) then (4,6),(5,7) of each eight
+                const uint32_t e = pp[2 * q4], o = pp[2 * q4 + 1];
+                const int base = (q4 >> 1) * 8 + (q4 & 1) * 4;
+                dst[base + 0] = (uint16_t)e;
+                dst[base + 1] = (uint16_t)o;
+                dst[base + 2] = (uint16_t)(e >> 16);
+                dst[base + 3] = (uint16_t)(o >> 16);
+            }
+        }
+        __syncthreads();
+
+        // ---- O_est: ordered FMA chain per channel, result exponents ----------------------------------
         if (tid < kD) {
             const int d = tid;
             float acc = 0.0f;
-            for (int i = 0; i < kk; ++i) {
-                const size_t row = bh * Ncap + sel_s[i];
-                const uint32_t hi = a.v_hi[row * kD + d];
-                const uint32_t mb = a.v_mid[row * (kD / 2) + d / 2], lb = a.v_lo[row * (kD / 2) + d / 2];
-                const uint32_t mn = (d & 1) ? (mb >> 4) : (mb & 15u), ln = (d & 1) ? (lb >> 4) : (lb & 15u);
-                acc = fmaf(phat_s[i], half_bits_to_float((hi << 8) | (mn << 4) | ln), acc);
-            }
+            for (int i = 0; i < kk; ++i) acc = fmaf(phat_s[i], half_bits_to_float(v_s[i][d]), acc);
             const int E = float_exp_field(acc) - 127;
             ehat = E < ehat ? E : ehat;
             if (a.dbg.oest) a.dbg.oest[hq * kD + d] = acc;

@@ -14,14 +14,22 @@ namespace akv {
 // row-independent test 1 + max_d w_d + s >= 3 (resp. 7).
 __device__ __forceinline__ uint32_t clamp_byte(int v) { return (uint32_t)(v < 0 ? 0 : (v > 128 ? 128 : v)); }
 
+// Workgroup = kVWaves waves, one (sequence, KV head, 512-token chunk); each wave owns 128 consecutive
+// token rows and walks them in batches of 32 (4 groups of 8 rows; lane -> row lane/8 of the group and the
+// 16-channel slice lane%8).  Per batch: decide the 32 rows from their HI bytes, issue the MID / LO loads of
+// the rows that need them, issue the HI loads of the next batch, and only then do the multiply-adds, so that
+// the dependent MID / LO fetch and the next HI fetch are both in flight behind the arithmetic.
 template <int G, bool DEBUG>
 __global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
 {
     __shared__ float red_s[kVWaves][G][kD + 1];
+    constexpr int kRowsPerWave = kVChunk / kVWaves;   // 128
+    constexpr int kGroups = 4;                        // row groups (of 8 rows) per batch
+    constexpr int kBatches = kRowsPerWave / (8 * kGroups);
 
     const int h = blockIdx.y, b = blockIdx.z, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane >> 3, cl = lane & 7;            // row within the wave's group of 8, channel slice 16*cl..16*cl+15
+    const int r = lane >> 3, cl = lane & 7;            // row within a group of 8, channel slice 16*cl..16*cl+15
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const int len = min(a.lens[b], Ncap);
     const int c0 = split * kVChunk;
@@ -52,8 +60,16 @@ __global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
         wmax = other > wmax ? other : wmax;
     }
     float Mg[G];
+    __amdgpu_buffer_rsrc_t rs_lg[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) Mg[g] = a.M[size_t(b) * Hq + size_t(h) * G + g];
+    for (int g = 0; g < G; ++g) {
+        const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
+        Mg[g] = a.M[hq];
+        rs_lg[g] = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
+    }
+    const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.v_hi + bh * Ncap * kD, uint32_t(Ncap) * kD);
+    const __amdgpu_buffer_rsrc_t rs_mid = make_rsrc(a.v_mid + bh * Ncap * (kD / 2), uint32_t(Ncap) * (kD / 2));
+    const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(a.v_lo + bh * Ncap * (kD / 2), uint32_t(Ncap) * (kD / 2));
 
     float acc[G][16], z[G];
 #pragma unroll
@@ -63,78 +79,105 @@ __global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
     }
 
-    // ---- stream the chunk: 32 token rows per step per workgroup, 8 per wave ----------------------------
-    for (int it = 0; it < kVChunk / (8 * kVWaves); ++it) {
-        const int t = c0 + it * (8 * kVWaves) + wave * 8 + r;
-        const bool valid = t < len;
-        const size_t row = bh * Ncap + (valid ? t : 0);
-        uint4 hi = make_uint4(0, 0, 0, 0);
-        if (valid) hi = *reinterpret_cast<const uint4*>(a.v_hi + row * kD + cl * 16);
-        float p[G];
-        int ahat = kAMin;
+    const int t_wave = c0 + wave * kRowsPerWave + r;
+    u32x4_t hc[kGroups], hn[kGroups];       // HI bytes of the current / the next batch
+    float lc[kGroups][G], ln[kGroups][G];   // logits of the current / the next batch
+    auto load_batch = [&](int bt, u32x4_t (&hh)[kGroups], float (&ll)[kGroups][G]) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float l = valid ? a.logits[(size_t(b) * Hq + size_t(h) * G + g) * Ncap + t] : Mg[g];
-            const float x = score_x(l, Mg[g], a.c);
-            const int ag = score_a(x);
-            ahat = ag > ahat ? ag : ahat;
-            p[g] = valid ? __builtin_amdgcn_exp2f(x) : 0.0f;
+        for (int gr = 0; gr < kGroups; ++gr) {
+            const int t = t_wave + bt * (8 * kGroups) + gr * 8;
+            const bool valid = t < len && bt < kBatches;
+            hh[gr] = buf_load_b128(rs_hi, valid ? uint32_t(t) * kD + cl * 16 : kSkip);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                ll[gr][g] = __builtin_bit_cast(float, buf_load_b32(rs_lg[g], valid ? uint32_t(t) * 4u : kSkip));
         }
-        // row decision (Rule 2), byte-parallel over the lane's 16 channels
-        const uint32_t ssplat = (uint32_t)(ahat + 64) * 0x01010101u;
-        const uint32_t hw[4] = {hi.x, hi.y, hi.z, hi.w};
-        uint32_t any1 = 0, any2 = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t evp = (hw[i] >> 2) & 0x1F1F1F1Fu;
-            any1 |= evp + B1[i] + ssplat;
-            any2 |= evp + B2[i] + ssplat;
-        }
-        const uint64_t b1 = __ballot((any1 & 0x80808080u) != 0), b2 = __ballot((any2 & 0x80808080u) != 0);
-        const int sh = lane & 56;
-        const bool need1 = ((b1 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 3);
-        const bool need2 = ((b2 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 7);
-        int applied = need2 ? 2 : (need1 ? 1 : 0);
-        if (a.force_level >= 0) applied = a.force_level;
+    };
+    load_batch(0, hc, lc);
 
-        uint2 mid = make_uint2(kFill8, kFill8);                        // level 0: unread bits 1000 0000
-        uint2 lo = applied == 1 ? make_uint2(kFill8, kFill8) : make_uint2(0u, 0u);   // level 1: unread bits 1000
-        if (valid && applied >= 1) mid = *reinterpret_cast<const uint2*>(a.v_mid + row * (kD / 2) + cl * 8);
-        if (valid && applied >= 2) lo = *reinterpret_cast<const uint2*>(a.v_lo + row * (kD / 2) + cl * 8);
+#pragma unroll 1
+    for (int bt = 0; bt < kBatches; ++bt) {
+        float p[kGroups][G];
+        u32x2_t mid[kGroups], lo[kGroups];
+        uint32_t fill[kGroups];
+        // decisions of the batch, then its MID / LO loads
+#pragma unroll
+        for (int gr = 0; gr < kGroups; ++gr) {
+            const int t = t_wave + bt * (8 * kGroups) + gr * 8;
+            const bool valid = t < len;
+            int ahat = kAMin;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float x = score_x(lc[gr][g], Mg[g], a.c);
+                const int ag = score_a(x);
+                ahat = ag > ahat ? ag : ahat;
+                p[gr][g] = valid ? __builtin_amdgcn_exp2f(x) : 0.0f;
+            }
+            const uint32_t ssplat = (uint32_t)(ahat + 64) * 0x01010101u;
+            const uint32_t hw[4] = {hc[gr].x, hc[gr].y, hc[gr].z, hc[gr].w};
+            uint32_t any1 = 0, any2 = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t evp = (hw[i] >> 2) & 0x1F1F1F1Fu;
+                any1 |= evp + B1[i] + ssplat;
+                any2 |= evp + B2[i] + ssplat;
+            }
+            const uint64_t b1 = __ballot((any1 & 0x80808080u) != 0), b2 = __ballot((any2 & 0x80808080u) != 0);
+            const int sh = lane & 56;
+            const bool need1 = ((b1 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 3);
+            const bool need2 = ((b2 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 7);
+            int applied = need2 ? 2 : (need1 ? 1 : 0);
+            if (a.force_level >= 0) applied = a.force_level;
+            const uint32_t off = uint32_t(t) * (kD / 2) + cl * 8;
+            mid[gr] = buf_load_b64(rs_mid, (valid && applied >= 1) ? off : kSkip);
+            lo[gr] = buf_load_b64(rs_lo, (valid && applied >= 2) ? off : kSkip);
+            fill[gr] = fill_for_level(applied);
 
-        if (DEBUG && valid) {
-            if (a.dbg.appliedV && cl == 0) a.dbg.appliedV[bh * Ncap + t] = (uint8_t)applied;
-            if (a.dbg.needV) {
-                uint32_t nv[4];
+            if (DEBUG && valid) {
+                if (a.dbg.appliedV && cl == 0) a.dbg.appliedV[bh * Ncap + t] = (uint8_t)applied;
+                if (a.dbg.needV) {
+                    uint32_t nv[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    nv[i] = 0;
+                    for (int i = 0; i < 4; ++i) {
+                        nv[i] = 0;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        int ev = (int)((hw[i] >> (8 * k + 2)) & 31u);
-                        ev = ev < 1 ? 1 : ev;
-                        int need = level_for_mantissa_bits(10 + a.guard_bits - (ehat[i * 4 + k] - (ahat + ev - 15)));
-                        if (a.force_level >= 0) need = a.force_level;
-                        nv[i] |= (uint32_t)need << (8 * k);
+                        for (int k = 0; k < 4; ++k) {
+                            int ev = (int)((hw[i] >> (8 * k + 2)) & 31u);
+                            ev = ev < 1 ? 1 : ev;
+                            int need = level_for_mantissa_bits(10 + a.guard_bits - (ehat[i * 4 + k] - (ahat + ev - 15)));
+                            if (a.force_level >= 0) need = a.force_level;
+                            nv[i] |= (uint32_t)need << (8 * k);
+                        }
                     }
+                    *reinterpret_cast<uint4*>(a.dbg.needV + (bh * Ncap + t) * kD + cl * 16) =
+                        make_uint4(nv[0], nv[1], nv[2], nv[3]);
                 }
-                *reinterpret_cast<uint4*>(a.dbg.needV + (bh * Ncap + t) * kD + cl * 16) =
-                    make_uint4(nv[0], nv[1], nv[2], nv[3]);
             }
         }
-
-        uint32_t pa[4], pb[4];
-        assemble8(hi.x, hi.y, mid.x, lo.x, pa);   // channels 0..7 of the slice
-        assemble8(hi.z, hi.w, mid.y, lo.y, pb);   // channels 8..15
-        const float v[16] = {lo_half(pa[0]), lo_half(pa[1]), hi_half(pa[0]), hi_half(pa[1]),
-                             lo_half(pa[2]), lo_half(pa[3]), hi_half(pa[2]), hi_half(pa[3]),
-                             lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
-                             lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
+        // HI bytes and logits of the next batch go in flight behind the MID / LO loads
+        load_batch(bt + 1, hn, ln);   // past the wave's rows every offset is kSkip: nothing is fetched
+        // multiply-adds of the batch
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            z[g] += p[g];
+        for (int gr = 0; gr < kGroups; ++gr) {
+            uint32_t pa[4], pb[4];
+            assemble8_fill(hc[gr].x, hc[gr].y, mid[gr].x, lo[gr].x, fill[gr], pa);   // channels 0..7 of the slice
+            assemble8_fill(hc[gr].z, hc[gr].w, mid[gr].y, lo[gr].y, fill[gr], pb);   // channels 8..15
+            const float v[16] = {lo_half(pa[0]), lo_half(pa[1]), hi_half(pa[0]), hi_half(pa[1]),
+                                 lo_half(pa[2]), lo_half(pa[3]), hi_half(pa[2]), hi_half(pa[3]),
+                                 lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
+                                 lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(p[g], v[i], acc[g][i]);
+            for (int g = 0; g < G; ++g) {
+                z[g] += p[gr][g];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(p[gr][g], v[i], acc[g][i]);
+            }
+        }
+#pragma unroll
+        for (int gr = 0; gr < kGroups; ++gr) {
+            hc[gr] = hn[gr];
+#pragma unroll
+            for (int g = 0; g < G; ++g) lc[gr][g] = ln[gr][g];
         }
     }
 

@@ -64,7 +64,7 @@ typedef struct akv_sizes {
     size_t v_hi, v_mid, v_lo; /* V planes                                              */
     size_t colmax;            /* uint16 [B][Hkv][D]                                    */
     size_t lens;              /* int32  [B]                                            */
-    size_t flags;             /* int32  [AKV_NFLAGS]                                   */
+    size_t flags;             /* int32  [AKV_NFLAGS + B]                               */
     size_t workspace;         /* scratch of akv_decode_attention (256-B aligned)       */
     size_t fp16_workspace;    /* scratch of akv_fp16_decode_attention (256-B aligned)  */
 } akv_sizes;
@@ -83,7 +83,8 @@ typedef struct akv_sizes {
  *   v_lo  [B][Hkv][Ncap][D/2]    last 4 bits, same packing
  *   colmax[B][Hkv][D] uint16     max over stored tokens of (k & 0x7fff)   (K_colmax)
  *   lens  [B] int32              tokens stored per sequence
- *   flags [AKV_NFLAGS] int32     sticky device-side status words
+ *   flags [AKV_NFLAGS + B] int32 sticky device-side status words, then one arrival counter per sequence
+ *                                used inside akv_append (zero between calls)
  * Slots that were never written hold zero after akv_cache_reset.
  */
 typedef struct akv_cache {
@@ -116,9 +117,13 @@ typedef struct akv_params {
     int32_t out_dtype;    /* 0: out is float32 [B][Hq][D]; 1: out is fp16 [B][Hq][D]                 */
     int32_t max_len;      /* host-known upper bound of lens[] used to size the launch; 0 means Ncap  */
     const akv_debug *dbg; /* host pointer to a struct of device pointers, or NULL                    */
-    void *const *events;  /* host pointer to 4 hipEvent_t, or NULL: the library records them on the
-                             stream before the K pass, after it, after the mid step and after the V
-                             pass + combine, so that a caller can time each kernel in place         */
+    void *const *events;  /* host pointer to 3 hipEvent_t, or NULL: the library records them on the
+                             stream before its first kernel, between the K kernel and the V kernel of
+                             the token-split path (on the head-per-workgroup path, which is one kernel:
+                             right after event 0) and after its last kernel, so that a caller can time
+                             the kernels in place                                                   */
+    int32_t path;         /* 0: choose; 1: head-per-workgroup path (one kernel; needs Hq/Hkv <= 4);
+                             2: token-split path (two kernels).  Both give the same decisions.       */
 } akv_params;
 
 #define AKV_MAX_TOPK 64
@@ -151,12 +156,21 @@ akv_status akv_append(const akv_cache *cache, const uint16_t *k_new, const uint1
                       int32_t n, void *stream);
 
 /*
+ * Prepare a decode workspace: zero its control words (arrival counters that the
+ * kernels of akv_decode_attention leave at zero again on exit).  Call it once on
+ * every workspace before its first use, and again if anything else wrote to it.
+ * For callers that cannot know: it is a single small fill kernel on the stream.
+ */
+akv_status akv_workspace_init(const akv_shape *shape, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Decode attention for one query token per sequence over the cache (sections
  * "Quantization of K-Cache", "Quantization of V-Cache", "Runtime of
  * AlignedKV").  q: device fp16 [B][Hq][D].  out: device [B][Hq][D] of
  * params->out_dtype.  A sequence with lens[b] == 0 yields zeros.  workspace:
- * device scratch of at least akv_sizes.workspace bytes, 256-B aligned; its
- * contents are undefined afterwards; concurrent calls need distinct workspaces.
+ * device scratch of at least akv_sizes.workspace bytes, 256-B aligned, prepared
+ * by akv_workspace_init; apart from its control words its contents are undefined
+ * afterwards; concurrent calls need distinct workspaces.
  * params may be NULL (defaults: adaptive, topk 32, guard 0, float32 out).
  */
 akv_status akv_decode_attention(const akv_cache *cache, const uint16_t *q, void *out, const akv_params *params,

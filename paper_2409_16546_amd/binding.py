@@ -19,7 +19,7 @@ AKV_OK, AKV_EINVAL, AKV_EWORKSPACE, AKV_EHIP = 0, 1, 2, 3
 AKV_TB = 256
 AKV_NFLAGS = 4
 AKV_MAX_TOPK = 64
-EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append",
+EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
            "akv_decode_attention", "akv_unpack", "akv_fp16_decode_attention"]
 
 
@@ -50,7 +50,7 @@ class akv_debug(C.Structure):
 class akv_params(C.Structure):
     _fields_ = [("scale", C.c_float), ("topk", C.c_int32), ("guard_bits", C.c_int32), ("force_level", C.c_int32),
                 ("out_dtype", C.c_int32), ("max_len", C.c_int32), ("dbg", C.POINTER(akv_debug)),
-                ("events", C.POINTER(C.c_void_p))]
+                ("events", C.POINTER(C.c_void_p)), ("path", C.c_int32)]
 
 
 _lib = None
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
         L.akv_cache_reset.argtypes = [C.POINTER(akv_cache), C.c_void_p]
         L.akv_append.restype = C.c_int
         L.akv_append.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.akv_workspace_init.restype = C.c_int
+        L.akv_workspace_init.argtypes = [C.POINTER(akv_shape), C.c_void_p, C.c_size_t, C.c_void_p]
         L.akv_decode_attention.restype = C.c_int
         L.akv_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.POINTER(akv_params), C.c_void_p,
                                            C.c_size_t, C.c_void_p]
@@ -139,8 +141,9 @@ class Cache:
         c = Cache(B, Hq, Hkv, D, Ncap, u8(sz.k_hi), u8(sz.k_mid), u8(sz.k_lo), u8(sz.v_hi), u8(sz.v_mid), u8(sz.v_lo),
                   torch.empty(B * Hkv * D, dtype=torch.int16, device=device),
                   torch.empty(B, dtype=torch.int32, device=device),
-                  torch.empty(AKV_NFLAGS, dtype=torch.int32, device=device), u8(sz.workspace), sz)
+                  torch.empty(AKV_NFLAGS + B, dtype=torch.int32, device=device), u8(sz.workspace), sz)
         akv_cache_reset(c)
+        akv_workspace_init(c, c.workspace)
         return c
 
     def struct(self) -> akv_cache:
@@ -154,6 +157,12 @@ class Cache:
 def akv_cache_reset(cache: Cache) -> None:
     s = cache.struct()
     _check(lib().akv_cache_reset(C.byref(s), _stream()))
+
+
+def akv_workspace_init(cache: Cache, workspace: torch.Tensor) -> None:
+    """Zero the control words of a decode workspace (once per workspace, before its first use)."""
+    shp = akv_shape(cache.B, cache.Hq, cache.Hkv, cache.D, cache.Ncap)
+    _check(lib().akv_workspace_init(C.byref(shp), _ptr(workspace), workspace.numel(), _stream()))
 
 
 def akv_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, n_new: torch.Tensor | None = None) -> None:
@@ -205,9 +214,10 @@ class DebugBuffers:
 def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None = None, *, scale: float = 0.0,
                          topk: int = 32, guard_bits: int = 0, force_level: int = -1, max_len: int = 0,
                          dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None,
-                         events=None) -> torch.Tensor:
+                         events=None, path: int = 0) -> torch.Tensor:
     """q: fp16 [B, Hq, D] on the device; out: float32 or fp16 [B, Hq, D] (allocated if None).
-    events: None or a ctypes array of 4 hipEvent_t handles the library records between its kernels."""
+    events: None or a ctypes array of 3 hipEvent_t handles the library records around its kernels.
+    path: 0 choose, 1 head-per-workgroup kernel, 2 token-split kernels."""
     assert q.dtype == torch.float16 and tuple(q.shape) == (cache.B, cache.Hq, cache.D)
     if out is None:
         out = torch.empty(cache.B, cache.Hq, cache.D, dtype=torch.float32, device=q.device)
@@ -215,7 +225,7 @@ def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None
     ws = cache.workspace if workspace is None else workspace
     d = dbg.struct() if dbg is not None else None
     p = akv_params(scale, topk, guard_bits, force_level, 0 if out.dtype == torch.float32 else 1, max_len,
-                   C.pointer(d) if d is not None else None, events)
+                   C.pointer(d) if d is not None else None, events, path)
     s = cache.struct()
     _check(lib().akv_decode_attention(C.byref(s), _ptr(q), _ptr(out), C.byref(p), _ptr(ws), ws.numel(), _stream()))
     return out

@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "akv_common.h"
@@ -61,7 +62,7 @@ akv_status akv_layout_sizes(const akv_shape* shape, akv_sizes* out)
     out->v_hi = e; out->v_mid = e / 2; out->v_lo = e / 2;
     out->colmax = size_t(shape->B) * shape->Hkv * shape->D * sizeof(uint16_t);
     out->lens = size_t(shape->B) * sizeof(int32_t);
-    out->flags = AKV_NFLAGS * sizeof(int32_t);
+    out->flags = (AKV_NFLAGS + size_t(shape->B)) * sizeof(int32_t);
     out->workspace = akv::ws_layout(*shape).total;
     out->fp16_workspace = akv::fp16_workspace_bytes(*shape);
     return AKV_OK;
@@ -81,6 +82,19 @@ akv_status akv_cache_reset(const akv_cache* cache, void* stream)
         if (reinterpret_cast<uintptr_t>(bf.p) % 16) return fail(AKV_EINVAL, "cache buffers must be 16-byte aligned");
         if (hipError_t e = akv::launch_zero(bf.p, bf.n, s)) return hip_fail(e, "zero launch");
     }
+    return AKV_OK;
+}
+
+akv_status akv_workspace_init(const akv_shape* shape, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!shape || !shape_ok(*shape)) return fail(AKV_EINVAL, "bad shape");
+    const akv::WsLayout w = akv::ws_layout(*shape);
+    if (!workspace || workspace_bytes < w.total)
+        return fail(AKV_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, w.total);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(AKV_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (hipError_t e = akv::launch_zero(static_cast<char*>(workspace) + w.control, akv::align256(w.control_bytes),
+                                        static_cast<hipStream_t>(stream)))
+        return hip_fail(e, "zero launch");
     return AKV_OK;
 }
 
@@ -135,6 +149,10 @@ akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void*
     a.c = (float)(scale * 1.4426950408889634);
     a.topk = p.topk; a.guard_bits = p.guard_bits; a.force_level = p.force_level; a.out_dtype = p.out_dtype;
     a.max_len = p.max_len > 0 ? p.max_len : a.s.Ncap;
+    {   // K-pass tile: 256-token tiles (one contiguous run per load) unless that makes too many short waves
+        const char* env = std::getenv("AKV_KTPL");
+        a.ktpl = env ? (std::atoi(env) == 8 ? 8 : 4) : 4;
+    }
     char* ws = static_cast<char*>(workspace);
     a.logits = reinterpret_cast<float*>(ws + w.logits);
     a.tilemax = reinterpret_cast<float*>(ws + w.tilemax);
@@ -142,21 +160,31 @@ akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void*
     a.Ehat = reinterpret_cast<int32_t*>(ws + w.Ehat);
     a.partO = reinterpret_cast<float*>(ws + w.partO);
     a.partZ = reinterpret_cast<float*>(ws + w.partZ);
+    a.kcount = reinterpret_cast<int32_t*>(ws + w.control);
+    a.vcount = a.kcount + size_t(a.s.B) * a.s.Hkv;
     if (p.dbg) {
         a.dbg = *p.dbg;
         if (a.dbg.logits) a.logits = a.dbg.logits;   // same shape: the pass writes the export directly
     }
+    if (p.path < 0 || p.path > 2) return fail(AKV_EINVAL, "path = %d out of range 0..2", p.path);
+    if (p.path == 1 && !akv::head_path_supported(a.s))
+        return fail(AKV_EINVAL, "path 1 (head per workgroup) needs Hq/Hkv <= 4");
+    // enough (sequence, KV head) pairs to fill the 256 compute units -> one workgroup per pair
+    const bool head_path = p.path == 1 || (p.path == 0 && akv::head_path_supported(a.s) &&
+                                           a.s.B * a.s.Hkv >= 192 && a.max_len <= 16384);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    auto mark = [&](int i) -> hipError_t {
-        return p.events ? hipEventRecord(static_cast<hipEvent_t>(p.events[i]), s) : hipSuccess;
-    };
-    if (hipError_t e = mark(0)) return hip_fail(e, "hipEventRecord");
-    if (hipError_t e = akv::launch_kpass(a, s)) return hip_fail(e, "K pass launch");
-    if (hipError_t e = mark(1)) return hip_fail(e, "hipEventRecord");
-    if (hipError_t e = akv::launch_mid(a, s)) return hip_fail(e, "mid step launch");
-    if (hipError_t e = mark(2)) return hip_fail(e, "hipEventRecord");
-    if (hipError_t e = akv::launch_vpass(a, s)) return hip_fail(e, "V pass launch");
-    if (hipError_t e = mark(3)) return hip_fail(e, "hipEventRecord");
+    auto ev = [&](int i) -> hipEvent_t { return p.events ? static_cast<hipEvent_t>(p.events[i]) : nullptr; };
+    if (p.events)
+        if (hipError_t e = hipEventRecord(ev(0), s)) return hip_fail(e, "hipEventRecord");
+    if (head_path) {
+        if (p.events)
+            if (hipError_t e = hipEventRecord(ev(1), s)) return hip_fail(e, "hipEventRecord");
+        if (hipError_t e = akv::launch_decode_head(a, s)) return hip_fail(e, "decode (head path) launch");
+    } else {
+        if (hipError_t e = akv::launch_decode_split(a, s, ev(1))) return hip_fail(e, "decode (split path) launch");
+    }
+    if (p.events)
+        if (hipError_t e = hipEventRecord(ev(2), s)) return hip_fail(e, "hipEventRecord");
     return AKV_OK;
 }
 

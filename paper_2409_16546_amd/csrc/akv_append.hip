@@ -7,6 +7,7 @@ namespace akv {
 
 // One workgroup per (sequence, KV head), 128 threads: thread d owns K channel d (so it is the only writer
 // of that column's nibble bytes and of colmax[d]); threads 0..63 own the V nibble byte of channels 2d, 2d+1.
+// flags[AKV_NFLAGS + b] counts the workgroups of sequence b that are done (zero between calls).
 __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t* __restrict__ k_new,
                                                      const uint16_t* __restrict__ v_new,
                                                      const int32_t* __restrict__ n_new, int n)
@@ -16,8 +17,9 @@ __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t
     const int len = c.lens[b];
     int cnt = n_new ? n_new[b] : n;
     cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
-    if (len + cnt > Ncap) return;   // refused; the bump kernel counts it
+    const bool fits = len + cnt <= Ncap;   // else the sequence is left unchanged and the refusal is counted
     const size_t bh = size_t(b) * Hkv + h;
+    if (fits) {
     const uint16_t* kn = k_new + bh * n * kD;
     const uint16_t* vn = v_new + bh * n * kD;
     uint32_t cm = c.colmax[bh * kD + d];
@@ -47,18 +49,17 @@ __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t
         }
     }
     c.colmax[bh * kD + d] = (uint16_t)cm;
-}
-
-// Runs after append_kernel on the same stream: lens += n_new, or count the refusal.
-__global__ void bump_lens_kernel(akv_cache c, const int32_t* __restrict__ n_new, int n)
-{
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= c.shape.B) return;
-    int cnt = n_new ? n_new[b] : n;
-    cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
-    const int len = c.lens[b];
-    if (len + cnt > c.shape.Ncap) atomicAdd(&c.flags[AKV_FLAG_OVERFLOW], 1);
-    else c.lens[b] = len + cnt;
+    }
+    // The workgroup of the sequence that arrives last (every head has read lens[b] by then) moves the length.
+    __shared__ int last_s;
+    __syncthreads();
+    if (d == 0) last_s = atomicAdd(&c.flags[AKV_NFLAGS + b], 1) == Hkv - 1;
+    __syncthreads();
+    if (last_s && d == 0) {
+        c.flags[AKV_NFLAGS + b] = 0;
+        if (fits) c.lens[b] = len + cnt;
+        else atomicAdd(&c.flags[AKV_FLAG_OVERFLOW], 1);
+    }
 }
 
 hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
@@ -66,9 +67,6 @@ hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16
 {
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(append_kernel, dim3(c.shape.Hkv, c.shape.B), dim3(128), 0, st, c, k_new, v_new, n_new, n);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bump_lens_kernel, dim3((c.shape.B + 63) / 64), dim3(64), 0, st, c, n_new, n);
     return hipGetLastError();
 }
 

@@ -16,11 +16,8 @@ constexpr int kAMin = -64;         // floor of the score exponent
 constexpr int kBuckets = 65;       // exponent buckets 0..64 of the approximate top-k
 constexpr int kMaxG = 8;           // query heads per KV head supported
 
-// K pass: one wave covers kKTile tokens (each lane kKTpl consecutive tokens of one block).
-constexpr int kKTpl = 8;
-constexpr int kKTile = 64 * kKTpl;                 // 512 tokens = 2 blocks
+// K pass: one wave covers 64 * ktpl tokens (ktpl = 4 or 8 consecutive tokens per lane, chosen per launch).
 constexpr int kKWaves = 4;                         // waves per workgroup
-constexpr int kKTokensPerWg = kKTile * kKWaves;    // 2048
 // V pass: one workgroup covers kVChunk tokens; a wave reads 8 token rows per step.
 constexpr int kVWaves = 4;
 constexpr int kVChunk = 512;
@@ -28,16 +25,17 @@ constexpr int kVChunk = 512;
 // Offsets (bytes) into the decode workspace.
 struct WsLayout {
     size_t logits;   // float [B][Hq][Ncap]
-    size_t tilemax;  // float [B][Hq][k_tiles(Ncap)]
+    size_t tilemax;  // float [B][Hq][Ncap / 256]: per-wave-tile maxima of the K pass
     size_t M;        // float [B][Hq]
     size_t Ehat;     // int32 [B][Hkv][D]
     size_t partO;    // float [B][Hq][v_splits(Ncap)][D]
     size_t partZ;    // float [B][Hq][v_splits(Ncap)]
+    size_t control;  // int32 [2][B][Hkv]: arrival counters of the K pass and of the V pass (zero between calls)
+    size_t control_bytes;
     size_t total;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
-inline __host__ __device__ int k_tiles(int ntok) { return (ntok + kKTile - 1) / kKTile; }      // K-pass tiles covering ntok
 inline __host__ __device__ int v_splits(int ntok) { return (ntok + kVChunk - 1) / kVChunk; }   // V-pass chunks covering ntok
 
 inline WsLayout ws_layout(const akv_shape& s)
@@ -46,11 +44,14 @@ inline WsLayout ws_layout(const akv_shape& s)
     size_t off = 0;
     const size_t bhq = size_t(s.B) * s.Hq;
     w.logits = off;  off = align256(off + bhq * s.Ncap * sizeof(float));
-    w.tilemax = off; off = align256(off + bhq * k_tiles(s.Ncap) * sizeof(float));
+    w.tilemax = off; off = align256(off + bhq * (s.Ncap / kTB) * sizeof(float));
     w.M = off;       off = align256(off + bhq * sizeof(float));
     w.Ehat = off;    off = align256(off + size_t(s.B) * s.Hkv * kD * sizeof(int32_t));
     w.partO = off;   off = align256(off + bhq * v_splits(s.Ncap) * kD * sizeof(float));
     w.partZ = off;   off = align256(off + bhq * v_splits(s.Ncap) * sizeof(float));
+    w.control = off;
+    w.control_bytes = 2 * size_t(s.B) * s.Hkv * sizeof(int32_t);
+    off = align256(off + w.control_bytes);
     w.total = off;
     return w;
 }
@@ -65,12 +66,15 @@ struct DecodeArgs {
     void* out;
     float c;             // (float)(scale * log2(e))
     int topk, guard_bits, force_level, out_dtype, max_len;
+    int ktpl;            // tokens per lane of the K pass (4 or 8): its wave tile is 64 * ktpl tokens
     float* logits;       // [B][Hq][Ncap]
     float* tilemax;
     float* M;
     int32_t* Ehat;
     float* partO;
     float* partZ;
+    int32_t* kcount;     // [B][Hkv] arrival counters (zero on entry, zero on exit)
+    int32_t* vcount;
     akv_debug dbg;       // device pointers or NULL
 };
 
@@ -79,9 +83,9 @@ hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16
                          hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, hipStream_t st);
-hipError_t launch_kpass(const DecodeArgs& a, hipStream_t st);
-hipError_t launch_mid(const DecodeArgs& a, hipStream_t st);
-hipError_t launch_vpass(const DecodeArgs& a, hipStream_t st);
+hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event);   // K kernel, V kernel
+hipError_t launch_decode_head(const DecodeArgs& a, hipStream_t st);                         // one kernel, a head per workgroup
+bool head_path_supported(const akv_shape& s);
 hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v, const int32_t* lens, const uint16_t* q,
                        void* out, float scale, int out_dtype, int max_len, void* ws, hipStream_t st);
 size_t fp16_workspace_bytes(const akv_shape& s);
@@ -96,6 +100,8 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h)
     return (float)__builtin_bit_cast(_Float16, (uint16_t)h);   // exact
 }
 __device__ __forceinline__ uint32_t float_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+// takes the word BY VALUE: __builtin_bit_cast applied directly to a vector component (w.y) reads component 0
+__device__ __forceinline__ float bits_float(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ int float_exp_field(float f) { return (int)((float_bits(f) >> 23) & 0xFFu); }
 
 // smallest level keeping at least m mantissa bits (2 / 6 / 10 kept at level 0 / 1 / 2)
@@ -140,6 +146,36 @@ __device__ __forceinline__ u32x2_t buf_load_b64(__amdgpu_buffer_rsrc_t r, uint32
 __device__ __forceinline__ u32x4_t buf_load_b128(__amdgpu_buffer_rsrc_t r, uint32_t off)
 {
     return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+}
+
+// Data handed from one workgroup to another INSIDE a kernel (logits and tile maxima to the workgroup that
+// runs the mid step, split partials to the one that combines them).  The L2 caches of the eight XCDs are not
+// coherent with each other, and a device-scope fence writes back / invalidates a whole L2, which costs far
+// more than the data is worth.  So these few words are moved with device-scope relaxed accesses (sc1: written
+// through to memory, read from memory), the producer waits for its stores to be acknowledged before it takes
+// its ticket with a device-scope atomic, and the consumer issues its loads after it has seen the last ticket.
+constexpr int kAuxSc1 = 16;   // cache policy bit of raw buffer accesses: device (agent) scope
+__device__ __forceinline__ void store_agent(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_agent(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(int32_t* p, int32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all of this wave's earlier stores have been acknowledged (and the compiler keeps them above this point)
+__device__ __forceinline__ void stores_done()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+}
+__device__ __forceinline__ int take_ticket(int32_t* counter)
+{
+    return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Variant of assemble8 taking the fill for unread bits as a per-byte constant OR-ed into the low bytes:

@@ -2,56 +2,71 @@
 // result exponents Rule 2 aligns to.
 // "Quantization of V-Cache": the scores differ by orders of magnitude, so the product of a few of the
 // largest scores with their V rows estimates the result (O_est); an approximate top-k picks them.
+#pragma once
 #include "akv_common.h"
 
 namespace akv {
 
-constexpr int kMidThreads = 256;
+constexpr int kMidMaxWaves = 16;
 
-// One workgroup per (sequence, KV head); the G query heads of the group are handled one after another.
-// Logits are walked 1024 at a time (a float4 per thread); the selected V rows are fetched by all threads at
-// once into LDS so that O_est costs one memory latency, then each channel runs its ordered FMA chain.
-template <int G>
-__global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
+// LDS of the mid step (declared __shared__ by the kernel that runs it)
+struct MidShared {
+    float M[kMaxG];              // in: global max logit of every query head of the group (set by the caller)
+    int ehat[kD];                // out: result exponent per channel, min over the group
+    int cnt[kBuckets];
+    int wlt[kMidMaxWaves], weq[kMidMaxWaves];
+    int sel[AKV_MAX_TOPK];
+    float phat[AKV_MAX_TOPK];
+    uint16_t v[AKV_MAX_TOPK][kD];
+    int J, fromcut;
+};
+
+// Run by one workgroup of NT threads for one (sequence b, KV head h), after every logit of the pair is
+// visible to it and sm.M holds the global max logit of each query head; the G query heads of the group are
+// handled one after another.  CROSS: the logits were written by other workgroups of the same kernel and are
+// read at device scope.  Logits are walked 4*NT at a time (a float4 per thread); the selected V rows are
+// fetched by all threads at once into LDS so that O_est costs one memory latency, then each channel runs its
+// ordered FMA chain.  Results: a.M, a.Ehat (global, for a later kernel) and sm.ehat (LDS).
+template <int G, int NT, bool CROSS>
+__device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, MidShared& sm)
 {
-    constexpr int kWaves = kMidThreads / 64;
-    constexpr int kChunk = kMidThreads * 4;
-    __shared__ int cnt_s[kBuckets];
-    __shared__ float redf_s[kWaves];
-    __shared__ int wlt_s[kWaves], weq_s[kWaves];
-    __shared__ int sel_s[AKV_MAX_TOPK];
-    __shared__ float phat_s[AKV_MAX_TOPK];
-    __shared__ uint16_t v_s[AKV_MAX_TOPK][kD];
-    __shared__ int J_s, fromcut_s;
+    constexpr int kWaves = NT / 64;
+    constexpr int kChunk = NT * 4;
+    static_assert(kWaves <= kMidMaxWaves && NT >= kD, "workgroup size");
+    int (&cnt_s)[kBuckets] = sm.cnt;
+    int (&wlt_s)[kMidMaxWaves] = sm.wlt;
+    int (&weq_s)[kMidMaxWaves] = sm.weq;
+    int (&sel_s)[AKV_MAX_TOPK] = sm.sel;
+    float (&phat_s)[AKV_MAX_TOPK] = sm.phat;
+    uint16_t (&v_s)[AKV_MAX_TOPK][kD] = sm.v;
+    int& J_s = sm.J;
+    int& fromcut_s = sm.fromcut;
 
-    const int h = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const int len = min(a.lens[b], Ncap);
     const size_t bh = size_t(b) * Hkv + h;
-    const int ntile = k_tiles(Ncap);
     int ehat = 32767;   // min over the group of the result exponent of channel tid (tid < D)
 
     for (int g = 0; g < G; ++g) {
         const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
-        const float* lg = a.logits + hq * Ncap;
+        const __amdgpu_buffer_rsrc_t rs_lg = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
+        auto load4 = [&](int t0) -> float4 {   // Ncap % 256 == 0: the vector stays inside the row
+            const u32x4_t w = CROSS ? __builtin_amdgcn_raw_buffer_load_b128(rs_lg, uint32_t(t0) * 4u, 0, kAuxSc1)
+                                    : __builtin_amdgcn_raw_buffer_load_b128(rs_lg, uint32_t(t0) * 4u, 0, 0);
+            return make_float4(bits_float(w.x), bits_float(w.y), bits_float(w.z), bits_float(w.w));
+        };
         if (len == 0) {
             if (tid == 0) a.M[hq] = 0.0f;
             continue;
         }
-        // ---- M = max_t l_t (exact, order-free) ------------------------------------------------------
-        float m = -INFINITY;
-        for (int i = tid; i < k_tiles(len); i += kMidThreads) m = fmaxf(m, a.tilemax[hq * ntile + i]);
-        m = wave_max(m);
+        const float M = sm.M[g];
         if (tid < kBuckets) cnt_s[tid] = 0;
-        if (lane == 0) redf_s[wave] = m;
         __syncthreads();
-        float M = redf_s[0];
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, redf_s[w]);
 
         // ---- histogram of score exponents: bucket j = -a_t, 0..64 -------------------------------------
         for (int t0 = tid * 4; t0 < len; t0 += kChunk) {
-            const float4 l4 = *reinterpret_cast<const float4*>(lg + t0);   // Ncap % 256 == 0: the vector stays inside the row
+            const float4 l4 = load4(t0);
             const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -81,7 +96,7 @@ __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
             int j[4];
             int c_lt = 0, c_eq = 0;
             if (t0 < len) {
-                const float4 l4 = *reinterpret_cast<const float4*>(lg + t0);
+                const float4 l4 = load4(t0);
                 const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -141,7 +156,7 @@ __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
         __syncthreads();
 
         // ---- the selected rows at full 16 bits -> LDS (8 threads per row, all rows in flight together) ----
-        for (int row = tid >> 3; row < kk; row += kMidThreads / 8) {
+        for (int row = tid >> 3; row < kk; row += NT / 8) {
             const int cl = tid & 7;
             const size_t vrow = bh * Ncap + sel_s[row];
             const uint4 hi = *reinterpret_cast<const uint4*>(a.v_hi + vrow * kD + cl * 16);
@@ -178,23 +193,11 @@ __global__ __launch_bounds__(kMidThreads) void mid_kernel(DecodeArgs a)
         __syncthreads();
     }
     if (tid < kD) {
+        sm.ehat[tid] = ehat;
         a.Ehat[bh * kD + tid] = ehat;
         if (a.dbg.Ehat) a.dbg.Ehat[bh * kD + tid] = (int16_t)ehat;
     }
-}
-
-hipError_t launch_mid(const DecodeArgs& a, hipStream_t st)
-{
-    const int G = a.s.Hq / a.s.Hkv;
-    const dim3 grid(a.s.Hkv, a.s.B), block(kMidThreads);
-    switch (G) {
-        case 1: hipLaunchKernelGGL(mid_kernel<1>, grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL(mid_kernel<2>, grid, block, 0, st, a); break;
-        case 4: hipLaunchKernelGGL(mid_kernel<4>, grid, block, 0, st, a); break;
-        case 8: hipLaunchKernelGGL(mid_kernel<8>, grid, block, 0, st, a); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    __syncthreads();
 }
 
 }  // namespace akv

@@ -1,6 +1,8 @@
-// V side of decode attention: Rule 2 per element, fetch per token row, softmax weights, O = S V~.
+// V side of decode attention as device functions: Rule 2 per element, fetch per token row, softmax
+// weights, O = S V~.
 // "Quantization of V-Cache": with O_est known, every addend s_t * v_td is aligned to the precision of the
 // result (Rule 2); the bit width of the addend is the bit width V is read at.
+#pragma once
 #include "akv_common.h"
 
 namespace akv {
@@ -14,96 +16,88 @@ namespace akv {
 // row-independent test 1 + max_d w_d + s >= 3 (resp. 7).
 __device__ __forceinline__ uint32_t clamp_byte(int v) { return (uint32_t)(v < 0 ? 0 : (v > 128 ? 128 : v)); }
 
-// Workgroup = kVWaves waves, one (sequence, KV head, 512-token chunk); each wave owns 128 consecutive
-// token rows and walks them in batches of 32 (4 groups of 8 rows; lane -> row lane/8 of the group and the
-// 16-channel slice lane%8).  Per batch: decide the 32 rows from their HI bytes, issue the MID / LO loads of
-// the rows that need them, issue the HI loads of the next batch, and only then do the multiply-adds, so that
-// the dependent MID / LO fetch and the next HI fetch are both in flight behind the arithmetic.
-template <int G, bool DEBUG>
-__global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
-{
-    __shared__ float red_s[kVWaves][G][kD + 1];
-    constexpr int kRowsPerWave = kVChunk / kVWaves;   // 128
-    constexpr int kGroups = 4;                        // row groups (of 8 rows) per batch
-    constexpr int kBatches = kRowsPerWave / (8 * kGroups);
-
-    const int h = blockIdx.y, b = blockIdx.z, split = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane >> 3, cl = lane & 7;            // row within a group of 8, channel slice 16*cl..16*cl+15
-    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
-    const int len = min(a.lens[b], Ncap);
-    const int c0 = split * kVChunk;
-    if (c0 >= len) return;                              // uniform
-    const size_t bh = size_t(b) * Hkv + h;
-    const int nsplit = v_splits(Ncap);
-
-    // ---- per-lane constants of Rule 2 for its 16 channels ----------------------------------------
+// Per-lane constants of Rule 2 for the lane's 16 channels (lane -> channel slice 16 * (lane % 8))
+struct VRule {
     uint32_t B1[4], B2[4];
-    int ehat[16];
+    int ehat[16];   // only read by the variant that exports per-element needs
+    int wmax;       // max over all 128 channels of w_d
+};
+
+// ehat: the 128 result exponents of the KV head (global memory or LDS)
+__device__ __forceinline__ void v_rule_setup(const int* ehat, int guard_bits, VRule& vr)
+{
+    const int cl = threadIdx.x & 7;
     int wmax = -100000;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        B1[i] = 0;
-        B2[i] = 0;
+        vr.B1[i] = 0;
+        vr.B2[i] = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int e = a.Ehat[bh * kD + cl * 16 + i * 4 + k];
-            ehat[i * 4 + k] = e;
-            const int w = a.guard_bits - 5 - e;
+            const int e = ehat[cl * 16 + i * 4 + k];
+            vr.ehat[i * 4 + k] = e;
+            const int w = guard_bits - 5 - e;
             wmax = w > wmax ? w : wmax;
-            B1[i] |= clamp_byte(w + 61) << (8 * k);
-            B2[i] |= clamp_byte(w + 57) << (8 * k);
+            vr.B1[i] |= clamp_byte(w + 61) << (8 * k);
+            vr.B2[i] |= clamp_byte(w + 57) << (8 * k);
         }
     }
     for (int o = 1; o < 8; o <<= 1) {
         const int other = __shfl_xor(wmax, o);
         wmax = other > wmax ? other : wmax;
     }
-    float Mg[G];
+    vr.wmax = wmax;
+}
+
+// One wave walks token rows of (b, h) in batches of 32 (4 groups of 8 rows; lane -> row lane/8 of the group
+// and the 16-channel slice lane%8): batch i covers rows t_first + i*batch_stride .. +31, i < nbatches.  Per
+// batch: decide the 32 rows from their HI bytes, issue the MID / LO loads of the rows that need them, issue
+// the HI loads of the next batch, and only then do the multiply-adds, so that the dependent MID / LO fetch and
+// the next HI fetch are both in flight behind the arithmetic.  Rows at or past len contribute nothing.
+// acc / z accumulate sum_t p_t * v~_td and sum_t p_t per lane (to be reduced over the 8 row lanes, then over
+// waves, by the caller).
+template <int G, bool DEBUG>
+__device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
+                                       int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
+                                       float (&z)[G])
+{
+    constexpr int kGroups = 4;   // row groups (of 8 rows) per batch
+    const int lane = threadIdx.x & 63;
+    const int r = lane >> 3, cl = lane & 7;
+    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
+    const size_t bh = size_t(b) * Hkv + h;
+
     __amdgpu_buffer_rsrc_t rs_lg[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
-        Mg[g] = a.M[hq];
-        rs_lg[g] = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
-    }
+    for (int g = 0; g < G; ++g)
+        rs_lg[g] = make_rsrc(a.logits + (size_t(b) * Hq + size_t(h) * G + g) * Ncap, uint32_t(Ncap) * 4u);
     const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.v_hi + bh * Ncap * kD, uint32_t(Ncap) * kD);
     const __amdgpu_buffer_rsrc_t rs_mid = make_rsrc(a.v_mid + bh * Ncap * (kD / 2), uint32_t(Ncap) * (kD / 2));
     const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(a.v_lo + bh * Ncap * (kD / 2), uint32_t(Ncap) * (kD / 2));
 
-    float acc[G][16], z[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        z[g] = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
-    }
-
-    const int t_wave = c0 + wave * kRowsPerWave + r;
     u32x4_t hc[kGroups], hn[kGroups];       // HI bytes of the current / the next batch
     float lc[kGroups][G], ln[kGroups][G];   // logits of the current / the next batch
     auto load_batch = [&](int bt, u32x4_t (&hh)[kGroups], float (&ll)[kGroups][G]) {
 #pragma unroll
         for (int gr = 0; gr < kGroups; ++gr) {
-            const int t = t_wave + bt * (8 * kGroups) + gr * 8;
-            const bool valid = t < len && bt < kBatches;
+            const int t = t_first + bt * batch_stride + gr * 8 + r;
+            const bool valid = t < len && bt < nbatches;   // past the wave's rows: nothing is fetched
             hh[gr] = buf_load_b128(rs_hi, valid ? uint32_t(t) * kD + cl * 16 : kSkip);
 #pragma unroll
-            for (int g = 0; g < G; ++g)
-                ll[gr][g] = __builtin_bit_cast(float, buf_load_b32(rs_lg[g], valid ? uint32_t(t) * 4u : kSkip));
+            for (int g = 0; g < G; ++g) ll[gr][g] = bits_float(buf_load_b32(rs_lg[g], valid ? uint32_t(t) * 4u : kSkip));
         }
     };
     load_batch(0, hc, lc);
 
 #pragma unroll 1
-    for (int bt = 0; bt < kBatches; ++bt) {
+    for (int bt = 0; bt < nbatches; ++bt) {
         float p[kGroups][G];
         u32x2_t mid[kGroups], lo[kGroups];
         uint32_t fill[kGroups];
         // decisions of the batch, then its MID / LO loads
 #pragma unroll
         for (int gr = 0; gr < kGroups; ++gr) {
-            const int t = t_wave + bt * (8 * kGroups) + gr * 8;
+            const int t = t_first + bt * batch_stride + gr * 8 + r;
             const bool valid = t < len;
             int ahat = kAMin;
 #pragma unroll
@@ -119,13 +113,13 @@ __global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t evp = (hw[i] >> 2) & 0x1F1F1F1Fu;
-                any1 |= evp + B1[i] + ssplat;
-                any2 |= evp + B2[i] + ssplat;
+                any1 |= evp + vr.B1[i] + ssplat;
+                any2 |= evp + vr.B2[i] + ssplat;
             }
             const uint64_t b1 = __ballot((any1 & 0x80808080u) != 0), b2 = __ballot((any2 & 0x80808080u) != 0);
             const int sh = lane & 56;
-            const bool need1 = ((b1 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 3);
-            const bool need2 = ((b2 >> sh) & 0xFFu) != 0 || (ahat + 1 + wmax >= 7);
+            const bool need1 = ((b1 >> sh) & 0xFFu) != 0 || (ahat + 1 + vr.wmax >= 3);
+            const bool need2 = ((b2 >> sh) & 0xFFu) != 0 || (ahat + 1 + vr.wmax >= 7);
             int applied = need2 ? 2 : (need1 ? 1 : 0);
             if (a.force_level >= 0) applied = a.force_level;
             const uint32_t off = uint32_t(t) * (kD / 2) + cl * 8;
@@ -144,7 +138,7 @@ __global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
                         for (int k = 0; k < 4; ++k) {
                             int ev = (int)((hw[i] >> (8 * k + 2)) & 31u);
                             ev = ev < 1 ? 1 : ev;
-                            int need = level_for_mantissa_bits(10 + a.guard_bits - (ehat[i * 4 + k] - (ahat + ev - 15)));
+                            int need = level_for_mantissa_bits(10 + a.guard_bits - (vr.ehat[i * 4 + k] - (ahat + ev - 15)));
                             if (a.force_level >= 0) need = a.force_level;
                             nv[i] |= (uint32_t)need << (8 * k);
                         }
@@ -155,7 +149,7 @@ __global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
             }
         }
         // HI bytes and logits of the next batch go in flight behind the MID / LO loads
-        load_batch(bt + 1, hn, ln);   // past the wave's rows every offset is kSkip: nothing is fetched
+        load_batch(bt + 1, hn, ln);
         // multiply-adds of the batch
 #pragma unroll
         for (int gr = 0; gr < kGroups; ++gr) {
@@ -180,73 +174,27 @@ __global__ __launch_bounds__(64 * kVWaves) void vpass_kernel(DecodeArgs a)
             for (int g = 0; g < G; ++g) lc[gr][g] = ln[gr][g];
         }
     }
+}
 
-    // ---- reduce over the 8 rows of a wave, then over the waves ----------------------------------------
+// sum acc / z over the 8 row lanes of a wave (lanes with the same lane % 8); afterwards lanes 0..7 hold the
+// wave's totals for their channel slices
+template <int G>
+__device__ __forceinline__ void v_reduce_rows(float (&acc)[G][16], float (&z)[G])
+{
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < G; ++g)
         for (int o = 8; o < 64; o <<= 1) {
             z[g] += __shfl_xor(z[g], o);
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[g][i] += __shfl_xor(acc[g][i], o);
         }
-        if (r == 0) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) red_s[wave][g][cl * 16 + i] = acc[g][i];
-            if (cl == 0) red_s[wave][g][kD] = z[g];
-        }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * (kD + 1); idx += 64 * kVWaves) {
-        const int g = idx / (kD + 1), d = idx % (kD + 1);
-        float s = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kVWaves; ++w) s += red_s[w][g][d];
-        const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
-        if (d < kD) a.partO[(hq * nsplit + split) * kD + d] = s;
-        else a.partZ[hq * nsplit + split] = s;
-    }
 }
 
-// out = sum_splits O / sum_splits Z  (every split uses the same global max, so no rescaling)
-__global__ __launch_bounds__(kD) void combine_kernel(DecodeArgs a)
+// write out[b][h*G + g][:] = o / zsum for channel d (or zero for an empty sequence)
+__device__ __forceinline__ void store_out(const DecodeArgs& a, size_t hq, int d, float res)
 {
-    const int hq_i = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-    const int len = min(a.lens[b], a.s.Ncap);
-    const size_t hq = size_t(b) * a.s.Hq + hq_i;
-    const int nsplit = v_splits(a.s.Ncap), used = v_splits(len);
-    float o = 0.0f, zsum = 0.0f;
-    for (int s = 0; s < used; ++s) {
-        o += a.partO[(hq * nsplit + s) * kD + d];
-        zsum += a.partZ[hq * nsplit + s];
-    }
-    const float res = used > 0 ? o / zsum : 0.0f;
     if (a.out_dtype == 0) reinterpret_cast<float*>(a.out)[hq * kD + d] = res;
     else reinterpret_cast<_Float16*>(a.out)[hq * kD + d] = (_Float16)res;
-}
-
-template <int G>
-static void launch_vpass_g(const DecodeArgs& a, hipStream_t st)
-{
-    const dim3 grid(v_splits(a.max_len), a.s.Hkv, a.s.B), block(64 * kVWaves);
-    const bool debug = a.dbg.needV || a.dbg.appliedV;
-    if (debug) hipLaunchKernelGGL((vpass_kernel<G, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((vpass_kernel<G, false>), grid, block, 0, st, a);
-}
-
-hipError_t launch_vpass(const DecodeArgs& a, hipStream_t st)
-{
-    const int G = a.s.Hq / a.s.Hkv;
-    switch (G) {
-        case 1: launch_vpass_g<1>(a, st); break;
-        case 2: launch_vpass_g<2>(a, st); break;
-        case 4: launch_vpass_g<4>(a, st); break;
-        case 8: launch_vpass_g<8>(a, st); break;
-        default: return hipErrorInvalidValue;
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(combine_kernel, dim3(a.s.Hq, a.s.B), dim3(kD), 0, st, a);
-    return hipGetLastError();
 }
 
 }  // namespace akv

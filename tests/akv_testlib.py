@@ -71,8 +71,9 @@ def assert_decode_equal(g_out: torch.Tensor, d: A.DebugBuffers, r: O.DecodeResul
     return err, rl2
 
 
-def run_both(k, v, q, lens, Ncap=None, dev="cuda:0", **params):
-    """Build both caches from the same host tensors, decode on both sides with every export on."""
+def run_both(k, v, q, lens, Ncap=None, dev="cuda:0", path=0, **params):
+    """Build both caches from the same host tensors, decode on both sides with every export on.
+    path: 0 library's choice, 1 head-per-workgroup kernel, 2 token-split kernels (GPU side only)."""
     B, Hkv, N, D = k.shape
     Hq = q.shape[1]
     Ncap = Ncap or ((N + 255) // 256) * 256
@@ -80,7 +81,7 @@ def run_both(k, v, q, lens, Ncap=None, dev="cuda:0", **params):
     gc = gpu_cache(k, v, lens, Hq, Ncap, dev)
     topk = params.get("topk", 32)
     dbg = A.DebugBuffers.allocate(gc, topk=topk)
-    out = A.akv_decode_attention(gc, q.to(dev), dbg=dbg, **params)
+    out = A.akv_decode_attention(gc, q.to(dev), dbg=dbg, path=path, **params)
     torch.cuda.synchronize()
     r = O.decode_attention(oc, bits(q), **params)
     return gc, oc, out, dbg, r

@@ -38,7 +38,7 @@ def test_layout_sizes_is_a_host_computation(A):
     e = 8 * 32 * 4096 * 128
     assert (sz.k_hi, sz.k_mid, sz.k_lo, sz.v_hi, sz.v_mid, sz.v_lo) == (e, e // 2, e // 2, e, e // 2, e // 2)
     assert sz.k_hi + sz.k_mid + sz.k_lo == 2 * e  # planes hold exactly the fp16 bytes: lossless, no padding
-    assert sz.colmax == 8 * 32 * 128 * 2 and sz.lens == 32 and sz.flags == 16
+    assert sz.colmax == 8 * 32 * 128 * 2 and sz.lens == 32 and sz.flags == (4 + 8) * 4
     assert sz.workspace >= 8 * 32 * 4096 * 4 and sz.workspace % 256 == 0 and sz.fp16_workspace % 256 == 0
 
 

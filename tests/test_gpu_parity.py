@@ -92,13 +92,16 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("path", [1, 2], ids=["head-path", "split-path"])
 @pytest.mark.parametrize("name,cfg,over,lens,params", CASES, ids=[c[0] for c in CASES])
-def test_decode_matches_oracle(T, name, cfg, over, lens, params):
+def test_decode_matches_oracle(T, name, cfg, over, lens, params, path):
     from paper_2409_16546_amd import workloads
-    say(f"decode parity: {name} cfg={cfg} {over} lens={lens} params={params}")
     w = workloads.make(cfg, **over)
+    if path == 1 and w.Hq // w.Hkv > 4:
+        pytest.skip("the head-per-workgroup kernel covers Hq/Hkv <= 4")
+    say(f"decode parity: {name} cfg={cfg} {over} lens={lens} params={params} path={path}")
     lens = w.lens.tolist() if lens is None else lens
-    gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, **params)
+    gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, path=path, **params)
     T.assert_cache_equal(gc, oc)
     err, rl2 = T.assert_decode_equal(out, dbg, r, lens, w.Hq // w.Hkv, name)
     say(f"  max-abs {err:.2e} rel-L2 {rl2:.2e} levels K {np.bincount(r.lvlK.ravel(), minlength=3)} "
@@ -110,8 +113,9 @@ def test_decode_edge_lengths_empty_one_and_smallest_capacity(T):
     say("decode parity: lens 0 / 1 / 255 / 256, Ncap 256")
     w = workloads.make(2, B=4, Hq=4, Hkv=2, N=256)
     lens = [0, 1, 255, 256]
-    gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, Ncap=256)
-    T.assert_decode_equal(out, dbg, r, lens, 2, "edge-lens")
+    for path in (1, 2):
+        gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, Ncap=256, path=path)
+        T.assert_decode_equal(out, dbg, r, lens, 2, f"edge-lens path {path}")
 
 
 def test_decode_raw_bit_patterns_with_zeros_and_subnormals(T):
@@ -122,9 +126,10 @@ def test_decode_raw_bit_patterns_with_zeros_and_subnormals(T):
     v = (v.float().clamp(-100, 100)).to(torch.float16)
     q = workloads.make(1, B=1, Hq=2, Hkv=2, N=256).q
     lens = [640]
-    gc, oc, out, dbg, r = T.run_both(k, v, q, lens)
-    T.assert_cache_equal(gc, oc)
-    T.assert_decode_equal(out, dbg, r, lens, 1, "raw-bits")
+    for path in (1, 2):
+        gc, oc, out, dbg, r = T.run_both(k, v, q, lens, path=path)
+        T.assert_cache_equal(gc, oc)
+        T.assert_decode_equal(out, dbg, r, lens, 1, f"raw-bits path {path}")
 
 
 def test_decode_is_deterministic_and_fp16_output(T):
@@ -133,12 +138,13 @@ def test_decode_is_deterministic_and_fp16_output(T):
     w = workloads.make(2, B=2, Hq=4, Hkv=4, N=1024)
     gc = T.gpu_cache(w.k, w.v, w.lens.tolist(), w.Hq, 1024)
     q = w.q.to(DEV)
-    o1 = A.akv_decode_attention(gc, q).clone()
-    o2 = A.akv_decode_attention(gc, q).clone()
-    o16 = A.akv_decode_attention(gc, q, out=torch.empty_like(q))
-    torch.cuda.synchronize()
-    assert torch.equal(o1, o2)
-    assert torch.equal(o16, o1.to(torch.float16))
+    for path in (1, 2):
+        o1 = A.akv_decode_attention(gc, q, path=path).clone()
+        o2 = A.akv_decode_attention(gc, q, path=path).clone()
+        o16 = A.akv_decode_attention(gc, q, out=torch.empty_like(q), path=path)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2)
+        assert torch.equal(o16, o1.to(torch.float16))
 
 
 def test_max_len_hint_gives_the_same_result(T):
@@ -147,10 +153,11 @@ def test_max_len_hint_gives_the_same_result(T):
     w = workloads.make(2, B=2, Hq=2, Hkv=2, N=700)
     gc = T.gpu_cache(w.k, w.v, [700, 300], w.Hq, 4096)
     q = w.q.to(DEV)
-    o1 = A.akv_decode_attention(gc, q).clone()
-    o2 = A.akv_decode_attention(gc, q, max_len=700).clone()
-    torch.cuda.synchronize()
-    assert torch.equal(o1, o2)
+    for path in (1, 2):
+        o1 = A.akv_decode_attention(gc, q, path=path).clone()
+        o2 = A.akv_decode_attention(gc, q, max_len=700, path=path).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2)
 
 
 def test_bad_arguments_are_refused_on_the_host(T):
@@ -163,7 +170,7 @@ def test_bad_arguments_are_refused_on_the_host(T):
         A.akv_layout_sizes(1, 4, 4, 128, 300)
     gc = A.Cache.allocate(1, 2, 2, 128, 256, DEV)
     q = torch.zeros(1, 2, 128, dtype=torch.float16, device=DEV)
-    for bad in (dict(topk=65), dict(guard_bits=13), dict(force_level=3), dict(max_len=257)):
+    for bad in (dict(topk=65), dict(guard_bits=13), dict(force_level=3), dict(max_len=257), dict(path=3)):
         with pytest.raises(A.AkvError) as e:
             A.akv_decode_attention(gc, q, **bad)
         assert e.value.status == A.AKV_EINVAL
@@ -206,11 +213,13 @@ def test_cfg2_full_size_sampled_against_oracle(T):
     N = 4096
     gc = T.gpu_cache(w.k, w.v, w.lens.tolist(), w.Hq, N)
     q = w.q.to(DEV)
-    out_plain = A.akv_decode_attention(gc, q, max_len=N).clone()       # the benchmarked launch
+    out_plain = A.akv_decode_attention(gc, q, max_len=N).clone()       # the benchmarked launch (library's choice of path)
     dbg = A.DebugBuffers.allocate(gc)
     out_dbg = A.akv_decode_attention(gc, q, max_len=N, dbg=dbg)
+    out_split = A.akv_decode_attention(gc, q, max_len=N, path=2)       # the other path, same masks
     torch.cuda.synchronize()
     assert torch.equal(out_plain, out_dbg)                              # exports do not change the result
+    assert (out_plain - out_split).abs().max().item() <= 1e-4          # summation order differs between the paths
     rng = np.random.default_rng(0)
     for b, h in zip(rng.integers(0, 8, 6), rng.integers(0, 32, 6)):
         b, h = int(b), int(h)

@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--copies", type=int, default=4, help="cache copies the steps rotate over")
+    ap.add_argument("--copies", type=int, default=8, help="cache copies the steps rotate over")
     ap.add_argument("--guard-bits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the fp16 / control-group / parity legs")
@@ -85,22 +85,22 @@ def main():
     G = Hq // Hkv
     steps, warmup = args.steps, args.warmup
     R = max(args.copies, (steps + warmup + 255) // 256)
-    visits = (steps + warmup + R - 1) // R + 2
-    Ncap = N + 256                                      # room for the tokens the timed steps append
-    log(f"[bench] workload {w.name}; {R} cache copies, Ncap {Ncap}, generated in {time.time() - t_start:.1f}s")
+    visits = (steps + warmup + R - 1) // R          # times each cache copy is stepped
+    N0 = N - visits                                 # tokens in each copy before its first step
+    Ncap = N
+    log(f"[bench] workload {w.name}; {R} cache copies, each stepped {visits} times from context {N0 + 1} to {N}; "
+        f"generated in {time.time() - t_start:.1f}s")
 
     kd, vd, qd = w.k.to(dev), w.v.to(dev), w.q.to(dev)
     caches = []
     for r in range(R):
         c = A.Cache.allocate(B, Hq, Hkv, D, Ncap, dev)
-        A.akv_append(c, kd[:, :, :N - 1].contiguous(), vd[:, :, :N - 1].contiguous())   # context N-1; the step adds one
+        A.akv_append(c, kd[:, :, :N0].contiguous(), vd[:, :, :N0].contiguous())
         caches.append(c)
-    # the tokens the steps append: the workload's last token first, then fresh draws of the same law
-    gen = torch.Generator().manual_seed(4242)
-    kn = (torch.randn(visits, B, Hkv, 1, D, generator=gen) * (w.k[:, :, :64].float().std(dim=2, keepdim=True))).to(torch.float16)
-    vn = (torch.randn(visits, B, Hkv, 1, D, generator=gen) * (w.v[:, :, :64].float().std(dim=2, keepdim=True))).to(torch.float16)
-    kn[0], vn[0] = w.k[:, :, N - 1:N], w.v[:, :, N - 1:N]
-    kn, vn = kn.to(dev), vn.to(dev)
+    # the tokens the steps append are the workload's own tokens N0 .. N-1, so the last step of every copy
+    # attends over exactly the workload
+    kn = [kd[:, :, N0 + i].contiguous() for i in range(visits)]
+    vn = [vd[:, :, N0 + i].contiguous() for i in range(visits)]
     outs = [torch.empty(B, Hq, D, dtype=torch.float32, device=dev) for _ in range(R)]
     visit_of = [0] * R
 
@@ -108,8 +108,8 @@ def main():
         r = i % R
         vi = visit_of[r]
         visit_of[r] += 1
-        A.akv_append(caches[r], kn[vi], vn[vi])
-        A.akv_decode_attention(caches[r], qd, outs[r], guard_bits=args.guard_bits, max_len=Ncap, events=events)
+        A.akv_append_decode_attention(caches[r], kn[vi], vn[vi], qd, outs[r], guard_bits=args.guard_bits, max_len=Ncap,
+                                      events=events)
 
     # ---------------------------------------------------------------- the timed region
     for i in range(warmup):
@@ -121,14 +121,14 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
-    log(f"[bench] {steps} steps: {ms_per_step * 1e3:.1f} us/step (context {N}..{N + max(visit_of) - 1})")
+    log(f"[bench] {steps} steps: {ms_per_step * 1e3:.1f} us/step (contexts {N0 + 1}..{N})")
 
     # ---------------------------------------------------------------- per-kernel durations (HIP events, same stream)
     ev = HipEvents()
     stream = torch.cuda.current_stream().cuda_stream
-    nprof = min(steps, 64)
-    for c in caches:                                     # back to context N-1 so the profile matches the timed steps
-        c.lens.fill_(N - 1)
+    nprof = min(steps, visits * R)
+    for c in caches:                                     # back to the initial context: the profile replays the timed steps
+        c.lens.fill_(N0)
     visit_of = [0] * R
     sets = [ev.create(3) for _ in range(nprof)]
     torch.cuda.synchronize()
@@ -141,9 +141,9 @@ def main():
     k_us, mid_us, v_us = kern_us, 0.0, 0.0
 
     # ---------------------------------------------------------------- algorithmic bytes (from the exported decisions)
-    c0 = A.Cache.allocate(B, Hq, Hkv, D, Ncap, dev)       # a fresh cache with exactly the workload's N tokens
-    A.akv_append(c0, kd[:, :, :N - 1].contiguous(), vd[:, :, :N - 1].contiguous())
-    A.akv_append(c0, kd[:, :, N - 1:N].contiguous(), vd[:, :, N - 1:N].contiguous())
+    for c in caches:                                     # every copy now holds exactly the workload's N tokens
+        c.lens.fill_(N)
+    c0 = caches[0]
     dbg = A.DebugBuffers.allocate(c0, want_needV=False)
     out_dbg = A.akv_decode_attention(c0, qd, guard_bits=args.guard_bits, max_len=Ncap, dbg=dbg).clone()
     torch.cuda.synchronize()
@@ -168,10 +168,10 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "BASELINE config 2: Llama-2-7B-shaped layer, batch 8, 32 heads (MHA), head_dim 128, "
-                               "context 4096 (+ the token each timed step appends), fp16 K/V N(0,1) x per-channel "
+                               "context 4096 (each timed step appends one token; contexts of the timed steps end at 4096), fp16 K/V N(0,1) x per-channel "
                                "log-uniform scales in [0.1,10], q N(0,1), seed 1002",
                    "B": B, "Hq": Hq, "Hkv": Hkv, "D": D, "context": N, "guard_bits": args.guard_bits, "topk": 32,
-                   "cache_copies_rotated": R, "step": "akv_append(1 token/seq) + akv_decode_attention"},
+                   "cache_copies_rotated": R, "step": "akv_append_decode_attention (append 1 token/seq + decode attention, one kernel)"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2)},
@@ -209,8 +209,6 @@ def main():
 
         fp16_us = timed(lambda i: A.akv_fp16_decode_attention(kcopies[i % R], vcopies[i % R], lens_n, qd, o16, max_len=Ncap,
                                                              workspace=ws16), steps)
-        for c in caches:
-            c.lens.fill_(N)
         ctl_us = timed(lambda i: A.akv_decode_attention(caches[i % R], qd, outs[i % R], force_level=2, max_len=Ncap), steps)
         akv_only_us = timed(lambda i: A.akv_decode_attention(caches[i % R], qd, outs[i % R], guard_bits=args.guard_bits,
                                                              max_len=Ncap), steps)

@@ -176,6 +176,18 @@ akv_status akv_workspace_init(const akv_shape *shape, void *workspace, size_t wo
 akv_status akv_decode_attention(const akv_cache *cache, const uint16_t *q, void *out, const akv_params *params,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * One decode step in one call: append one token per sequence (k_new, v_new:
+ * device fp16 [B][Hkv][D], as akv_append with n = 1 and n_new = NULL), then
+ * akv_decode_attention over the cache including that token.  Same results as
+ * the two calls in a row; on the head-per-workgroup path both run in one
+ * kernel.  A sequence that is already full keeps its tokens (the refusal is
+ * counted in flags[AKV_FLAG_OVERFLOW]) and is attended as it is.
+ */
+akv_status akv_append_decode_attention(const akv_cache *cache, const uint16_t *k_new, const uint16_t *v_new,
+                                       const uint16_t *q, void *out, const akv_params *params, void *workspace,
+                                       size_t workspace_bytes, void *stream);
+
 /* Lossless inverse of append: planes -> device fp16 k_out, v_out [B][Hkv][Ncap][D]
  * (all Ncap slots; unwritten slots give zero).  Either output may be NULL. */
 akv_status akv_unpack(const akv_cache *cache, uint16_t *k_out, uint16_t *v_out, void *stream);

@@ -20,7 +20,7 @@ AKV_TB = 256
 AKV_NFLAGS = 4
 AKV_MAX_TOPK = 64
 EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
-           "akv_decode_attention", "akv_unpack", "akv_fp16_decode_attention"]
+           "akv_decode_attention", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention"]
 
 
 class AkvError(RuntimeError):
@@ -77,6 +77,9 @@ def lib() -> C.CDLL:
         L.akv_decode_attention.restype = C.c_int
         L.akv_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.POINTER(akv_params), C.c_void_p,
                                            C.c_size_t, C.c_void_p]
+        L.akv_append_decode_attention.restype = C.c_int
+        L.akv_append_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                  C.POINTER(akv_params), C.c_void_p, C.c_size_t, C.c_void_p]
         L.akv_unpack.restype = C.c_int
         L.akv_unpack.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p]
         L.akv_fp16_decode_attention.restype = C.c_int
@@ -228,6 +231,28 @@ def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None
                    C.pointer(d) if d is not None else None, events, path)
     s = cache.struct()
     _check(lib().akv_decode_attention(C.byref(s), _ptr(q), _ptr(out), C.byref(p), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def akv_append_decode_attention(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor,
+                                out: torch.Tensor | None = None, *, scale: float = 0.0, topk: int = 32,
+                                guard_bits: int = 0, force_level: int = -1, max_len: int = 0,
+                                dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None, events=None,
+                                path: int = 0) -> torch.Tensor:
+    """One decode step: append k_new, v_new (fp16 [B, Hkv, 1, D] or [B, Hkv, D]) and attend with q."""
+    assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16 and k_new.numel() == cache.B * cache.Hkv * cache.D
+    assert v_new.numel() == k_new.numel()
+    assert q.dtype == torch.float16 and tuple(q.shape) == (cache.B, cache.Hq, cache.D)
+    if out is None:
+        out = torch.empty(cache.B, cache.Hq, cache.D, dtype=torch.float32, device=q.device)
+    assert out.dtype in (torch.float32, torch.float16) and tuple(out.shape) == tuple(q.shape)
+    ws = cache.workspace if workspace is None else workspace
+    d = dbg.struct() if dbg is not None else None
+    p = akv_params(scale, topk, guard_bits, force_level, 0 if out.dtype == torch.float32 else 1, max_len,
+                   C.pointer(d) if d is not None else None, events, path)
+    s = cache.struct()
+    _check(lib().akv_append_decode_attention(C.byref(s), _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(out), C.byref(p),
+                                             _ptr(ws), ws.numel(), _stream()))
     return out
 
 

@@ -118,8 +118,13 @@ akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, 
     return AKV_OK;
 }
 
-akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void* out, const akv_params* params,
-                                void* workspace, size_t workspace_bytes, void* stream)
+}  // extern "C"
+
+namespace {
+
+// decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])
+akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, void* out,
+                       const akv_params* params, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (akv_status st = check_cache(cache)) return st;
     if (!q || !out) return fail(AKV_EINVAL, "q / out is NULL");
@@ -145,6 +150,7 @@ akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void*
     a.k_hi = cache->k_hi; a.k_mid = cache->k_mid; a.k_lo = cache->k_lo;
     a.v_hi = cache->v_hi; a.v_mid = cache->v_mid; a.v_lo = cache->v_lo;
     a.colmax = cache->colmax; a.lens = cache->lens; a.q = q; a.out = out;
+    a.flags = cache->flags;
     const double scale = p.scale > 0.0f ? (double)p.scale : 1.0 / std::sqrt((double)a.s.D);
     a.c = (float)(scale * 1.4426950408889634);
     a.topk = p.topk; a.guard_bits = p.guard_bits; a.force_level = p.force_level; a.out_dtype = p.out_dtype;
@@ -179,13 +185,35 @@ akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void*
     if (head_path) {
         if (p.events)
             if (hipError_t e = hipEventRecord(ev(1), s)) return hip_fail(e, "hipEventRecord");
+        a.k_new = k_new;   // the head kernel stores the new token itself
+        a.v_new = v_new;
         if (hipError_t e = akv::launch_decode_head(a, s)) return hip_fail(e, "decode (head path) launch");
     } else {
+        if (k_new)
+            if (hipError_t e = akv::launch_append(*cache, k_new, v_new, nullptr, 1, s)) return hip_fail(e, "append launch");
         if (hipError_t e = akv::launch_decode_split(a, s, ev(1))) return hip_fail(e, "decode (split path) launch");
     }
     if (p.events)
         if (hipError_t e = hipEventRecord(ev(2), s)) return hip_fail(e, "hipEventRecord");
     return AKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void* out, const akv_params* params,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_impl(cache, nullptr, nullptr, q, out, params, workspace, workspace_bytes, stream);
+}
+
+akv_status akv_append_decode_attention(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new,
+                                       const uint16_t* q, void* out, const akv_params* params, void* workspace,
+                                       size_t workspace_bytes, void* stream)
+{
+    if (!k_new || !v_new) return fail(AKV_EINVAL, "k_new / v_new is NULL");
+    return decode_impl(cache, k_new, v_new, q, out, params, workspace, workspace_bytes, stream);
 }
 
 akv_status akv_fp16_decode_attention(const akv_shape* shape, const uint16_t* k, const uint16_t* v, const int32_t* lens,

@@ -13,7 +13,7 @@ __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t
                                                      const int32_t* __restrict__ n_new, int n)
 {
     const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-    const int Hkv = c.shape.Hkv, Ncap = c.shape.Ncap, NB = Ncap / kTB;
+    const int Hkv = c.shape.Hkv, Ncap = c.shape.Ncap;
     const int len = c.lens[b];
     int cnt = n_new ? n_new[b] : n;
     cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
@@ -24,29 +24,9 @@ __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t
     const uint16_t* vn = v_new + bh * n * kD;
     uint32_t cm = c.colmax[bh * kD + d];
     for (int i = 0; i < cnt; ++i) {
-        const int t = len + i, blk = t / kTB, j = t % kTB;
-        const uint32_t kx = kn[size_t(i) * kD + d];
-        const size_t col = (bh * NB + blk) * kD + d;
-        c.k_hi[col * kTB + j] = (uint8_t)(kx >> 8);
-        uint8_t* pm = c.k_mid + col * (kTB / 2) + j / 2;
-        uint8_t* pl = c.k_lo + col * (kTB / 2) + j / 2;
-        if (j & 1) {
-            *pm = (uint8_t)((*pm & 0x0F) | (((kx >> 4) & 15u) << 4));
-            *pl = (uint8_t)((*pl & 0x0F) | ((kx & 15u) << 4));
-        } else {
-            *pm = (uint8_t)((*pm & 0xF0) | ((kx >> 4) & 15u));
-            *pl = (uint8_t)((*pl & 0xF0) | (kx & 15u));
-        }
-        const uint32_t mag = kx & 0x7FFFu;   // |k| as bits: integer order is magnitude order
+        const uint32_t mag = store_token(c.k_hi, c.k_mid, c.k_lo, c.v_hi, c.v_mid, c.v_lo, bh, Ncap, len + i, d,
+                                         kn + size_t(i) * kD, vn + size_t(i) * kD);
         cm = mag > cm ? mag : cm;
-        const size_t row = bh * Ncap + t;
-        const uint32_t vx = vn[size_t(i) * kD + d];
-        c.v_hi[row * kD + d] = (uint8_t)(vx >> 8);
-        if (d < kD / 2) {
-            const uint32_t v0 = vn[size_t(i) * kD + 2 * d], v1 = vn[size_t(i) * kD + 2 * d + 1];
-            c.v_mid[row * (kD / 2) + d] = (uint8_t)(((v0 >> 4) & 15u) | (((v1 >> 4) & 15u) << 4));
-            c.v_lo[row * (kD / 2) + d] = (uint8_t)((v0 & 15u) | ((v1 & 15u) << 4));
-        }
     }
     c.colmax[bh * kD + d] = (uint16_t)cm;
     }

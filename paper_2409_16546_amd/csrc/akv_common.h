@@ -63,6 +63,8 @@ struct DecodeArgs {
     const uint16_t* colmax;
     const int32_t* lens;
     const uint16_t* q;
+    const uint16_t *k_new, *v_new;   // fused append of one token per sequence ([B][Hkv][D] each), or NULL
+    int32_t* flags;                  // cache flags (append arrival counters, overflow count); used with k_new
     void* out;
     float c;             // (float)(scale * log2(e))
     int topk, guard_bits, force_level, out_dtype, max_len;
@@ -79,6 +81,52 @@ struct DecodeArgs {
 };
 
 // host launchers (defined next to their kernels)
+// Store one token of one (sequence, KV head) at position t: thread d (0..127) owns K channel d and is the
+// only writer of that column's nibble bytes; threads 0..63 own the V nibble byte of channels 2d, 2d+1.
+// Returns |k| as bits (for K_colmax).  "Dynamic Quantization": all 16 bits are kept, in three planes.
+#if defined(__HIPCC__)
+// byte index (within k_mid / k_lo) of the nibble pair that holds token t of column d
+__device__ __forceinline__ size_t k_nibble_index(size_t bh, int Ncap, int t, int d)
+{
+    return ((bh * (Ncap / kTB) + t / kTB) * kD + d) * (kTB / 2) + (t % kTB) / 2;
+}
+// old_m, old_l: the current bytes at k_nibble_index (read by the caller, possibly long before)
+__device__ __forceinline__ uint32_t store_token_rmw(uint8_t* k_hi, uint8_t* k_mid, uint8_t* k_lo, uint8_t* v_hi,
+                                                    uint8_t* v_mid, uint8_t* v_lo, size_t bh, int Ncap, int t, int d,
+                                                    const uint16_t* krow, const uint16_t* vrow, uint32_t old_m,
+                                                    uint32_t old_l)
+{
+    const int NB = Ncap / kTB, blk = t / kTB, j = t % kTB;
+    const uint32_t kx = krow[d];
+    const size_t col = (bh * NB + blk) * kD + d;
+    k_hi[col * kTB + j] = (uint8_t)(kx >> 8);
+    const size_t nib = k_nibble_index(bh, Ncap, t, d);
+    if (j & 1) {
+        k_mid[nib] = (uint8_t)((old_m & 0x0F) | (((kx >> 4) & 15u) << 4));
+        k_lo[nib] = (uint8_t)((old_l & 0x0F) | ((kx & 15u) << 4));
+    } else {
+        k_mid[nib] = (uint8_t)((old_m & 0xF0) | ((kx >> 4) & 15u));
+        k_lo[nib] = (uint8_t)((old_l & 0xF0) | (kx & 15u));
+    }
+    const size_t row = bh * Ncap + t;
+    const uint32_t vx = vrow[d];
+    v_hi[row * kD + d] = (uint8_t)(vx >> 8);
+    if (d < kD / 2) {
+        const uint32_t v0 = vrow[2 * d], v1 = vrow[2 * d + 1];
+        v_mid[row * (kD / 2) + d] = (uint8_t)(((v0 >> 4) & 15u) | (((v1 >> 4) & 15u) << 4));
+        v_lo[row * (kD / 2) + d] = (uint8_t)((v0 & 15u) | ((v1 & 15u) << 4));
+    }
+    return kx & 0x7FFFu;   // |k| as bits: integer order is magnitude order
+}
+__device__ __forceinline__ uint32_t store_token(uint8_t* k_hi, uint8_t* k_mid, uint8_t* k_lo, uint8_t* v_hi,
+                                                uint8_t* v_mid, uint8_t* v_lo, size_t bh, int Ncap, int t, int d,
+                                                const uint16_t* krow, const uint16_t* vrow)
+{
+    const size_t nib = k_nibble_index(bh, Ncap, t, d);
+    return store_token_rmw(k_hi, k_mid, k_lo, v_hi, v_mid, v_lo, bh, Ncap, t, d, krow, vrow, k_mid[nib], k_lo[nib]);
+}
+#endif
+
 hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
                          hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);

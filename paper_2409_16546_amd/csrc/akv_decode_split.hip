@@ -66,7 +66,7 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
         ms.M[tid] = m;
     }
     __syncthreads();
-    mid_step<G, 64 * kKWaves, true>(a, b, h, ms);
+    mid_step<G, 64 * kKWaves, true>(a, b, h, len, ms);
     if (tid == 0) store_agent(&a.kcount[bh], 0);   // ready for the next call
 }
 

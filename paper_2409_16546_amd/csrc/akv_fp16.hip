@@ -15,7 +15,8 @@ inline int f_splits(int ntok) { return (ntok + kFChunk - 1) / kFChunk; }
 size_t fp16_workspace_bytes(const akv_shape& s)
 {
     const size_t bhq = size_t(s.B) * s.Hq, ns = f_splits(s.Ncap);
-    return align256(bhq * ns * kD * sizeof(float)) + 2 * align256(bhq * ns * sizeof(float));
+    return align256(bhq * ns * kD * sizeof(float)) + 2 * align256(bhq * ns * sizeof(float)) +
+           align256(bhq * size_t(s.Ncap) * sizeof(float));   // split partials, then the logits of the head-per-workgroup variant
 }
 
 struct F16Args {
@@ -165,6 +166,151 @@ __global__ __launch_bounds__(kD) void fp16_combine_kernel(F16Args a)
     else reinterpret_cast<_Float16*>(a.out)[hq * kD + d] = (_Float16)res;
 }
 
+// Head-per-workgroup variant (the design of the plane kernels' main path): one workgroup of 1024 threads does
+// the whole (sequence, KV head): logits of all tokens (kept in the workspace), their maximum, then weights and
+// O.  A wave takes batches of 32 rows round-robin; the 8 row loads of the next batch are in flight while the
+// current batch is reduced.
+template <int G, int NT>
+__global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restrict__ logits)
+{
+    constexpr int kWaves = NT / 64;
+    constexpr int kLoads = 8;   // 4 rows each
+    __shared__ float max_s[kWaves][G];
+    __shared__ float red_s[kWaves][G][kD + 1];
+
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane >> 4, cl = lane & 15;
+    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
+    const int len = min(a.lens[b], Ncap);
+    if (len == 0) {
+        for (int idx = tid; idx < G * kD; idx += NT) {
+            const size_t o = (size_t(b) * Hq + size_t(h) * G) * kD + idx;
+            if (a.out_dtype == 0) reinterpret_cast<float*>(a.out)[o] = 0.0f;
+            else reinterpret_cast<_Float16*>(a.out)[o] = (_Float16)0.0f;
+        }
+        return;
+    }
+    const size_t bh = size_t(b) * Hkv + h;
+    const __amdgpu_buffer_rsrc_t rs_k = make_rsrc(a.k + bh * Ncap * kD, uint32_t(Ncap) * kD * 2u);
+    const __amdgpu_buffer_rsrc_t rs_v = make_rsrc(a.v + bh * Ncap * kD, uint32_t(Ncap) * kD * 2u);
+    float* lg[G];
+    float qf[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
+        lg[g] = logits + hq * Ncap;
+        const uint4 w = *reinterpret_cast<const uint4*>(a.q + hq * kD + cl * 8);
+        unpack8h(w, qf[g]);
+    }
+    const int nbatch = (len + 31) / 32;
+    auto load_batch = [&](const __amdgpu_buffer_rsrc_t& rs, int bt, u32x4_t (&w)[kLoads]) {
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int t = bt * 32 + j * 4 + r;
+            w[j] = buf_load_b128(rs, (bt < nbatch && t < len) ? uint32_t(t) * (kD * 2) + cl * 16 : kSkip);
+        }
+    };
+
+    // ---- phase 1: logits and their maximum ---------------------------------------------------------
+    float mloc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) mloc[g] = -INFINITY;
+    u32x4_t wc[kLoads], wn[kLoads];
+    load_batch(rs_k, wave, wc);
+#pragma unroll 1
+    for (int bt = wave; bt < nbatch; bt += kWaves) {
+        load_batch(rs_k, bt + kWaves, wn);
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int t = bt * 32 + j * 4 + r;
+            float kf[8];
+            unpack8h(make_uint4(wc[j].x, wc[j].y, wc[j].z, wc[j].w), kf);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float s = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) s = fmaf(qf[g][i], kf[i], s);
+                for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o);
+                if (t < len) {
+                    mloc[g] = fmaxf(mloc[g], s);
+                    if (cl == 0) lg[g][t] = s;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) wc[j] = wn[j];
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float m = wave_max(mloc[g]);
+        if (lane == 0) max_s[wave][g] = m;
+    }
+    __syncthreads();   // also: every logit store of the workgroup has completed
+    float mg[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        mg[g] = max_s[0][g];
+        for (int w = 1; w < kWaves; ++w) mg[g] = fmaxf(mg[g], max_s[w][g]);
+    }
+
+    // ---- phase 2: weights and O -----------------------------------------------------------------------
+    float acc[G][8], z[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        z[g] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[g][i] = 0.0f;
+    }
+    load_batch(rs_v, wave, wc);
+#pragma unroll 1
+    for (int bt = wave; bt < nbatch; bt += kWaves) {
+        load_batch(rs_v, bt + kWaves, wn);
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int t = bt * 32 + j * 4 + r;
+            float vf[8];
+            unpack8h(make_uint4(wc[j].x, wc[j].y, wc[j].z, wc[j].w), vf);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float p = t < len ? __builtin_amdgcn_exp2f((lg[g][t < len ? t : 0] - mg[g]) * a.c) : 0.0f;
+                z[g] += p;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[g][i] = fmaf(p, vf[i], acc[g][i]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) wc[j] = wn[j];
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        for (int o = 16; o < 64; o <<= 1) {
+            z[g] += __shfl_xor(z[g], o);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[g][i] += __shfl_xor(acc[g][i], o);
+        }
+        if (r == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) red_s[wave][g][cl * 8 + i] = acc[g][i];
+            if (cl == 0) red_s[wave][g][kD] = z[g];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * kD; idx += NT) {
+        const int g = idx / kD, d = idx % kD;
+        float o = 0.0f, zsum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            o += red_s[w][g][d];
+            zsum += red_s[w][g][kD];
+        }
+        const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
+        const float res = o / zsum;
+        if (a.out_dtype == 0) reinterpret_cast<float*>(a.out)[hq * kD + d] = res;
+        else reinterpret_cast<_Float16*>(a.out)[hq * kD + d] = (_Float16)res;
+    }
+}
+
 hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v, const int32_t* lens, const uint16_t* q,
                        void* out, float scale, int out_dtype, int max_len, void* ws, hipStream_t st)
 {
@@ -180,7 +326,15 @@ hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v,
     a.partM = reinterpret_cast<float*>(p);
     p += align256(bhq * a.nsplit * sizeof(float));
     a.partZ = reinterpret_cast<float*>(p);
+    p += align256(bhq * a.nsplit * sizeof(float));
+    float* logits = reinterpret_cast<float*>(p);
     const int G = s.Hq / s.Hkv;
+    if (G <= 2 && s.B * s.Hkv >= 192 && max_len <= 16384) {   // enough heads to fill the chip: one workgroup per head
+        const dim3 hgrid(s.Hkv, s.B);
+        if (G == 1) hipLaunchKernelGGL((fp16_head_kernel<1, 1024>), hgrid, dim3(1024), 0, st, a, logits);
+        else hipLaunchKernelGGL((fp16_head_kernel<2, 1024>), hgrid, dim3(1024), 0, st, a, logits);
+        return hipGetLastError();
+    }
     const dim3 grid(f_splits(max_len), s.Hkv, s.B), block(64 * kFWaves);
     switch (G) {
         case 1: hipLaunchKernelGGL(fp16_kernel<1>, grid, block, 0, st, a); break;

@@ -13,20 +13,29 @@ struct KShared {
     float q[G][kD];
     int emax[G];
     uint64_t need_mid[2], need_lo[2];   // bit d%64 of word d/64: column d is read at level >= 1 / = 2
+    float knew[kD];                     // fused append: the new token's K row as it will be read at the column levels
+    float new_logit[G];                 // fused append: q . knew, accumulated in channel order
 };
 
 // Rule 1 for the 128 columns of (b, h).  Called by every thread of a workgroup of at least 128 threads
 // (contains barriers); afterwards ks holds q as fp32 and the level masks.
+// k_new_bits: fp16 bits of channel tid of a token that is being appended in the same kernel (fused append),
+// else -1: K_colmax then counts that token, and the token's row, read at the column levels, is left in
+// ks.knew for new_token_logit().  Returns the K_colmax of channel tid (tid < 128) that the levels used.
 template <int G>
-__device__ __forceinline__ void k_levels(const DecodeArgs& a, int b, int h, KShared<G>& ks, bool export_levels)
+__device__ __forceinline__ uint32_t k_levels(const DecodeArgs& a, int b, int h, KShared<G>& ks, bool export_levels,
+                                             int k_new_bits = -1)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t bh = size_t(b) * a.s.Hkv + h;
     if (tid < G) ks.emax[tid] = -1;
     __syncthreads();
     float P[G];
+    uint32_t colmax_used = 0;
     if (tid < kD) {
         uint32_t cm = a.colmax[bh * kD + tid];
+        if (k_new_bits >= 0) cm = max(cm, uint32_t(k_new_bits) & 0x7FFFu);
+        colmax_used = cm;
         cm = cm < 0x0400u ? 0x0400u : cm;               // below the smallest normal: its places are 2^-14's
         const float cmf = half_bits_to_float(cm);
 #pragma unroll
@@ -54,8 +63,32 @@ __device__ __forceinline__ void k_levels(const DecodeArgs& a, int b, int h, KSha
             ks.need_lo[wave] = b2;
         }
         if (a.dbg.lvlK && export_levels) a.dbg.lvlK[bh * kD + tid] = (uint8_t)lv;
+        if (k_new_bits >= 0) {   // "Dynamic Quantization": bits that are not read are filled with 100...
+            const uint32_t kb = uint32_t(k_new_bits);
+            ks.knew[tid] = half_bits_to_float(lv == 2 ? kb : (lv == 1 ? ((kb & 0xFFF0u) | 0x0008u) : ((kb & 0xFF00u) | 0x0080u)));
+        }
     }
     __syncthreads();
+    return colmax_used;
+}
+
+// Fused append: the logit of the token that is being appended, from ks.knew, with the same arithmetic as a
+// tile lane (fp32, channels ascending).  One thread per query head of the group.
+template <int G>
+__device__ __forceinline__ float new_token_logit(const KShared<G>& ks, int g)
+{
+    float acc = 0.0f;
+    for (int d0 = 0; d0 < kD; d0 += 16) {   // operands fetched 16 at a time, the additions stay in channel order
+        float qv[16], kv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            qv[i] = ks.q[g][d0 + i];
+            kv[i] = ks.knew[d0 + i];
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc = fmaf(qv[i], kv[i], acc);
+    }
+    return acc;
 }
 
 __device__ __forceinline__ uint64_t uniform64(uint64_t v)

@@ -21,14 +21,14 @@ struct MidShared {
     int J, fromcut;
 };
 
-// Run by one workgroup of NT threads for one (sequence b, KV head h), after every logit of the pair is
+// Run by one workgroup of NT threads for one (sequence b, KV head h) of len tokens, after every logit of the pair is
 // visible to it and sm.M holds the global max logit of each query head; the G query heads of the group are
 // handled one after another.  CROSS: the logits were written by other workgroups of the same kernel and are
 // read at device scope.  Logits are walked 4*NT at a time (a float4 per thread); the selected V rows are
 // fetched by all threads at once into LDS so that O_est costs one memory latency, then each channel runs its
 // ordered FMA chain.  Results: a.M, a.Ehat (global, for a later kernel) and sm.ehat (LDS).
 template <int G, int NT, bool CROSS>
-__device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, MidShared& sm)
+__device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int len, MidShared& sm)
 {
     constexpr int kWaves = NT / 64;
     constexpr int kChunk = NT * 4;
@@ -44,7 +44,6 @@ __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, MidS
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
-    const int len = min(a.lens[b], Ncap);
     const size_t bh = size_t(b) * Hkv + h;
     int ehat = 32767;   // min over the group of the result exponent of channel tid (tid < D)
 

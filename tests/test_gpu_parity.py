@@ -132,6 +132,34 @@ def test_decode_raw_bit_patterns_with_zeros_and_subnormals(T):
         T.assert_decode_equal(out, dbg, r, lens, 1, f"raw-bits path {path}")
 
 
+@pytest.mark.parametrize("path", [1, 2], ids=["head-path", "split-path"])
+def test_append_decode_in_one_call_matches_oracle_step_by_step(T, path):
+    """Several decode steps in a row (append one token, attend), also into a sequence that is full."""
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    say(f"append + decode in one call, 6 steps, path {path}")
+    B, Hq, Hkv, Ncap = 3, 4, 2, 512
+    w = workloads.make(2, B=B, Hq=Hq, Hkv=Hkv, N=512)
+    lens0 = [250, 506, 0]                       # sequence 1 fills up after 6 steps; sequence 2 starts empty
+    oc = T.oracle_cache(w.k[:, :, :506], w.v[:, :, :506], lens0, Ncap)
+    gc = T.gpu_cache(w.k[:, :, :506], w.v[:, :, :506], lens0, Hq, Ncap)
+    gen = torch.Generator().manual_seed(9)
+    refused = 0
+    for step in range(8):
+        kn = (torch.randn(B, Hkv, 1, 128, generator=gen) * 3).to(torch.float16)
+        vn = torch.randn(B, Hkv, 1, 128, generator=gen).to(torch.float16)
+        q = torch.randn(B, Hq, 128, generator=gen).to(torch.float16)
+        refused += O.append(oc, T.bits(kn), T.bits(vn))
+        r = O.decode_attention(oc, T.bits(q))
+        dbg = A.DebugBuffers.allocate(gc)
+        out = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), q.to(DEV), dbg=dbg, path=path)
+        torch.cuda.synchronize()
+        T.assert_cache_equal(gc, oc)
+        T.assert_decode_equal(out, dbg, r, oc.lens.tolist(), Hq // Hkv, f"step {step}")
+    assert refused == 2 and int(gc.flags.cpu()[0]) == 2
+    assert not gc.flags.cpu()[A.AKV_NFLAGS:].any()          # the arrival counters are back at zero
+
+
 def test_decode_is_deterministic_and_fp16_output(T):
     from paper_2409_16546_amd import workloads, binding as A
     say("decode: run twice, bitwise equal; fp16 output = rounded fp32 output")
@@ -199,6 +227,27 @@ def test_fp16_yardstick_matches_textbook_attention(T, G):
     got = out.cpu().numpy().astype(np.float64)
     assert np.abs(got - ref).max() <= T.MAX_ABS and T.rel_l2(got, ref) <= T.REL_L2
     assert not got[2].any()
+
+
+@pytest.mark.parametrize("G", [1, 2])
+def test_fp16_yardstick_head_per_workgroup_variant(T, G):
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    say(f"fp16 yardstick, many heads (one workgroup per head): G={G}, ragged lengths incl. 0 and 1")
+    B, Hkv, N, Ncap = 24, 8, 700, 768
+    w = workloads.make(2, B=B, Hq=Hkv * G, Hkv=Hkv, N=N)
+    rng = np.random.default_rng(3)
+    lens = rng.integers(1, N + 1, size=B).astype(np.int32)
+    lens[0], lens[1], lens[2] = N, 0, 1
+    kp = torch.zeros(B, Hkv, Ncap, 128, dtype=torch.float16)
+    vp = torch.zeros_like(kp)
+    kp[:, :, :N], vp[:, :, :N] = w.k, w.v
+    out = A.akv_fp16_decode_attention(kp.to(DEV), vp.to(DEV), torch.from_numpy(lens).to(DEV), w.q.to(DEV))
+    torch.cuda.synchronize()
+    ref = O.fp16_attention(T.bits(kp), T.bits(vp), lens, T.bits(w.q))
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() <= T.MAX_ABS and T.rel_l2(got, ref) <= T.REL_L2
+    assert not got[1].any()
 
 
 # ------------------------------------------------------------------------------------------ full bench size, sampled

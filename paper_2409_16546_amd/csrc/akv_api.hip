@@ -155,10 +155,6 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     a.c = (float)(scale * 1.4426950408889634);
     a.topk = p.topk; a.guard_bits = p.guard_bits; a.force_level = p.force_level; a.out_dtype = p.out_dtype;
     a.max_len = p.max_len > 0 ? p.max_len : a.s.Ncap;
-    {   // K-pass tile: 256-token tiles (one contiguous run per load) unless that makes too many short waves
-        const char* env = std::getenv("AKV_KTPL");
-        a.ktpl = env ? (std::atoi(env) == 8 ? 8 : 4) : 4;
-    }
     char* ws = static_cast<char*>(workspace);
     a.logits = reinterpret_cast<float*>(ws + w.logits);
     a.tilemax = reinterpret_cast<float*>(ws + w.tilemax);

@@ -16,7 +16,7 @@ constexpr int kAMin = -64;         // floor of the score exponent
 constexpr int kBuckets = 65;       // exponent buckets 0..64 of the approximate top-k
 constexpr int kMaxG = 8;           // query heads per KV head supported
 
-// K pass: one wave covers 64 * ktpl tokens (ktpl = 4 or 8 consecutive tokens per lane, chosen per launch).
+// K pass: one wave covers one 256-token block (4 consecutive tokens per lane).
 constexpr int kKWaves = 4;                         // waves per workgroup
 // V pass: one workgroup covers kVChunk tokens; a wave reads 8 token rows per step.
 constexpr int kVWaves = 4;
@@ -68,7 +68,6 @@ struct DecodeArgs {
     void* out;
     float c;             // (float)(scale * log2(e))
     int topk, guard_bits, force_level, out_dtype, max_len;
-    int ktpl;            // tokens per lane of the K pass (4 or 8): its wave tile is 64 * ktpl tokens
     float* logits;       // [B][Hq][Ncap]
     float* tilemax;
     float* M;

@@ -10,10 +10,10 @@
 
 namespace akv {
 
-// lens[b] is shared by the heads of a sequence.  Every workgroup reads it at its start and then takes a ticket
-// (the atomic's result is not looked at before the end of the kernel, so nothing waits for it); the one that
-// drew the last ticket -- every head has read the old length by then -- stores the new length at its end, or
-// counts the refusal.
+// lens[b] is shared by the heads of a sequence.  Every workgroup reads it at its start and takes a ticket
+// later (thread 0, once its wave is done with its K tile and would otherwise idle at the barrier: the
+// round trip of the atomic costs nothing there); the one that drew the last ticket -- every head has read the
+// old length by then -- stores the new length at its end, or counts the refusal.
 __device__ __forceinline__ void finish_append(const DecodeArgs& a, int b, int len_old, int ticket)
 {
     if (!a.k_new || threadIdx.x != 0) return;
@@ -24,6 +24,9 @@ __device__ __forceinline__ void finish_append(const DecodeArgs& a, int b, int le
     }
 }
 
+// groups of 8 rows per batch of the V side: what the register budget of the launch shape allows
+template <int G, int NT> constexpr int head_v_groups() { return NT <= 512 && G <= 2 ? 4 : 2; }
+
 template <int G, int NT, bool DEBUG>
 __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
 {
@@ -32,6 +35,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     __shared__ MidShared ms;
     __shared__ float wmax_s[G][kWaves];
     __shared__ float red_s[kWaves][G][kD + 1];
+    __shared__ __align__(16) uint8_t kstage[kWaves][kKStage];
 
     const int h = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -40,15 +44,12 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     const size_t bh = size_t(b) * Hkv + h;
     __shared__ int len_s;
     int ticket = -1;
-    if (tid == 0) {
-        len_s = min(a.lens[b], Ncap);
-        if (a.k_new) {
-            stores_done();   // the length has been read (and parked in LDS) before the ticket is taken
-            ticket = take_ticket(&a.flags[AKV_NFLAGS + b]);
-        }
-    }
+    // q and K_colmax of the head are asked for first: everything below queues up behind them
+    KLevelsIn<G> lin;
+    k_levels_load<G>(a, b, h, lin);
+    if (tid == 0) len_s = min(a.lens[b], Ncap);
     __syncthreads();
-    const int len_old = len_s;
+    const int len_old = __builtin_amdgcn_readfirstlane(len_s);   // the same in every lane: keep it in a scalar register
     const bool appended = a.k_new && len_old + 1 <= Ncap;   // a full sequence keeps its tokens (counted at the end)
     // Fused append of one token: this workgroup owns every byte of (b, h).  The K side below runs over the
     // len_old tokens already stored and takes the new token's logit from its fp16 row directly, so nothing
@@ -69,8 +70,20 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
         return;
     }
 
-    // ---- K side: levels, then the tiles of the head round-robin over the waves ----------------------
-    const uint32_t colmax_used = k_levels<G>(a, b, h, ks, true, k_new_bits);
+    // ---- K side: levels, then the 256-token blocks of the head dealt over the waves ---------------------
+    // in contiguous, balanced ranges (sizes differ by at most one block)
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int nblk = (len_old + kTB - 1) / kTB;   // the tokens already stored
+    const int per = nblk / kWaves, extra = nblk % kWaves;
+    int blk = wave_u * per + min(wave_u, extra);
+    const int blk_end = blk + per + (wave_u < extra ? 1 : 0);
+    // The HI bytes of the wave's first block do not depend on the levels: they go in flight behind the loads of
+    // the level computation (issued at the top of the kernel) and arrive while it runs.
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+    u32x4_t kpre[4] = {zero4, zero4, zero4, zero4};
+    const bool pre_any = blk < blk_end;
+    if (pre_any) k_tile_pre(a, b, h, blk, kpre);
+    const uint32_t colmax_used = k_levels_finish<G>(a, b, h, ks, true, k_new_bits, lin);
     if (appended && tid >= NT - 64 && tid < NT - 64 + G) {   // a lane of the last wave per query head
         const int g = tid - (NT - 64);
         ks.new_logit[g] = new_token_logit<G>(ks, g);
@@ -78,28 +91,44 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     float wm[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) wm[g] = -INFINITY;
-    // The 256-token blocks of the head are dealt out in contiguous, balanced ranges (sizes differ by at most
-    // one block); a wave walks its range two blocks at a time (512-token tiles), then a last single block,
-    // so that e.g. 17 blocks on 16 waves still take one tile's time.
-    const int nblk = (len_old + kTB - 1) / kTB;   // the tokens already stored
-    const int per = nblk / kWaves, extra = nblk % kWaves;
-    int blk = wave * per + min(wave, extra);
-    const int blk_end = blk + per + (wave < extra ? 1 : 0);
-    while (blk < blk_end) {
-        float tm[G];
-        if (blk + 2 <= blk_end) {
-            k_tile<G, 8, 4>(a, b, h, blk, len_old, ks, 0, tm);
-            blk += 2;
-        } else {
-            k_tile<G, 4, 8>(a, b, h, blk, len_old, ks, 0, tm);
-            blk += 1;
-        }
+    auto fold = [&](const float (&tm)[G]) {
 #pragma unroll
         for (int g = 0; g < G; ++g) wm[g] = fmaxf(wm[g], tm[g]);
+    };
+    // own[g][i]: logit of token 4*tid + i if the wave's only block was block `wave` (at most kWaves blocks: the
+    // mid step then takes its logits from these registers instead of reading them back)
+    float own[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) own[g][i] = 0.0f;
+    uint8_t* stage = &kstage[wave_u][0];
+    if (pre_any) {   // the block whose first HI bytes are already in flight
+        float tm[G];
+        k_tile<G>(a, b, h, blk, len_old, ks, 0, tm, kpre, true, own, stage);
+        blk += 1;
+        fold(tm);
+    }
+    while (blk < blk_end) {
+        float tm[G], later[G][4];
+        k_tile<G>(a, b, h, blk, len_old, ks, 0, tm, kpre, false, later, stage);
+        blk += 1;
+        fold(tm);
     }
     if (lane == 0)
 #pragma unroll
         for (int g = 0; g < G; ++g) wmax_s[g][wave] = wm[g];
+    if (tid == 0 && a.k_new) {
+        stores_done();   // ordered after the read of the length
+        ticket = take_ticket(&a.flags[AKV_NFLAGS + b]);
+    }
+    // A wave that is done with its tiles has nothing to do until the mid step has run: it fetches the HI bytes
+    // of its first batch of V rows now (they depend on nothing).  Not when the row that is being appended lies
+    // in that range -- its bytes are stored below.
+    constexpr int KG = head_v_groups<G, NT>(), RB = 8 * KG;
+    const bool pre_ok = !(appended && len_old < RB * kWaves);
+    u32x4_t pre[KG];
+    v_prefetch_hi<KG>(a, b, h, wave * RB, pre_ok ? len : 0, pre);
     if (appended && tid < kD) {   // the new token goes into the planes (the block's lines were just read: they are in L2), K_colmax follows
         store_token_rmw(const_cast<uint8_t*>(a.k_hi), const_cast<uint8_t*>(a.k_mid), const_cast<uint8_t*>(a.k_lo),
                         const_cast<uint8_t*>(a.v_hi), const_cast<uint8_t*>(a.v_mid), const_cast<uint8_t*>(a.v_lo), bh,
@@ -119,11 +148,19 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     __syncthreads();
 
     // ---- mid step -----------------------------------------------------------------------------------
-    mid_step<G, NT, false>(a, b, h, len, ms);
+    const bool own_ok = nblk <= kWaves;   // then wave w < nblk has walked exactly block w, four tokens per lane
+    if (own_ok && appended && (len_old >> 2) == tid) {   // the new token's logit did not come from a tile
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if ((len_old & 3) == i) own[g][i] = ks.new_logit[g];
+    }
+    mid_step<G, NT, false>(a, b, h, len, ms, own, own_ok);
 
-    // ---- V side: batches of 32 rows round-robin over the waves ----------------------------------------
+    // ---- V side: batches of 8*KG rows round-robin over the waves ----------------------------------------
     VRule vr;
-    v_rule_setup(ms.ehat, a.guard_bits, vr);
+    v_rule_setup(ms.ehat, a.guard_bits, a.force_level, vr);
     float Mg[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) Mg[g] = ms.M[g];
@@ -134,9 +171,9 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
     }
-    const int nbatch = (len + 31) / 32;
+    const int nbatch = (len + RB - 1) / RB;
     const int mine = nbatch > wave ? (nbatch - wave + kWaves - 1) / kWaves : 0;
-    v_rows<G, DEBUG>(a, b, h, wave * 32, 32 * kWaves, mine, len, vr, Mg, acc, z);
+    v_rows<G, KG, DEBUG, true>(a, b, h, wave * RB, RB * kWaves, mine, len, vr, Mg, acc, z, pre, pre_ok);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll

@@ -1,6 +1,6 @@
 // Decode attention, token-split path: the tokens of every (sequence, KV head) are spread over many
 // workgroups (long contexts, few heads).  Two kernels:
-//   K kernel  Rule 1 levels + q.K~ over 64*TPL-token tiles; the workgroup of a (sequence, KV head) that
+//   K kernel  Rule 1 levels + q.K~, one 256-token block per wave; the workgroup of a (sequence, KV head) that
 //             finishes last runs the mid step (max, score exponents, top-k, O_est, result exponents);
 //   V kernel  Rule 2 + S.V~ over 512-token chunks; the workgroup that finishes last combines the chunks.
 // Sections "Quantization of K-Cache", "Quantization of V-Cache", "Runtime of AlignedKV".
@@ -11,10 +11,11 @@
 
 namespace akv {
 
-template <int G, int TPL>
+template <int G>
 __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
 {
-    constexpr int kTile = 64 * TPL;
+    constexpr int kTile = kTB;   // tokens per wave
+    __shared__ __align__(16) uint8_t kstage[kKWaves][kKStage];
     __shared__ KShared<G> ks;
     __shared__ MidShared ms;
     __shared__ float red_s[G][kKWaves];
@@ -25,16 +26,19 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
     const int len = min(a.lens[b], Ncap);
     const size_t bh = size_t(b) * Hkv + h;
-    const int tile = blockIdx.x * kKWaves + wave;
+    const int tile = blockIdx.x * kKWaves + __builtin_amdgcn_readfirstlane(wave);
     if (blockIdx.x * (kTile * kKWaves) >= len) return;   // whole workgroup beyond the sequence (uniform)
 
     k_levels<G>(a, b, h, ks, blockIdx.x == 0);
     if (tile * kTile < len) {                            // else this wave's tile is beyond the sequence
         float tm[G];
-        k_tile<G, TPL, 8>(a, b, h, tile * (kTile / kTB), len, ks, kAuxSc1, tm);
+        const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+        const u32x4_t none[4] = {zero4, zero4, zero4, zero4};
+        float lg[G][4];
+        k_tile<G>(a, b, h, tile, len, ks, kAuxSc1, tm, none, false, lg, &kstage[__builtin_amdgcn_readfirstlane(wave)][0]);
         if (lane == 0)
 #pragma unroll
-            for (int g = 0; g < G; ++g)   // NB slots per head: enough for either tile size
+            for (int g = 0; g < G; ++g)   // NB slots per head: one per block
                 store_agent(&a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + tile], tm[g]);
     }
 
@@ -66,7 +70,8 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
         ms.M[tid] = m;
     }
     __syncthreads();
-    mid_step<G, 64 * kKWaves, true>(a, b, h, len, ms);
+    const float none4[G][4] = {};
+    mid_step<G, 64 * kKWaves, true>(a, b, h, len, ms, none4, false);
     if (tid == 0) store_agent(&a.kcount[bh], 0);   // ready for the next call
 }
 
@@ -94,7 +99,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     }
 
     VRule vr;
-    v_rule_setup(a.Ehat + bh * kD, a.guard_bits, vr);
+    v_rule_setup(a.Ehat + bh * kD, a.guard_bits, a.force_level, vr);
     float Mg[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) Mg[g] = a.M[size_t(b) * Hq + size_t(h) * G + g];
@@ -105,7 +110,8 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
     }
-    v_rows<G, DEBUG>(a, b, h, c0 + wave * 32, 32 * kVWaves, kVChunk / (32 * kVWaves), len, vr, Mg, acc, z);
+    const u32x4_t none[4] = {};
+    v_rows<G, 4, DEBUG>(a, b, h, c0 + wave * 32, 32 * kVWaves, kVChunk / (32 * kVWaves), len, vr, Mg, acc, z, none, false);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll
@@ -150,10 +156,9 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 template <int G>
 static hipError_t launch_split_g(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event)
 {
-    const int tile = 64 * a.ktpl * kKWaves;
+    const int tile = kTB * kKWaves;   // tokens per workgroup of the K kernel: one 256-token block per wave
     const dim3 kgrid((a.max_len + tile - 1) / tile, a.s.Hkv, a.s.B), kblock(64 * kKWaves);
-    if (a.ktpl == 4) hipLaunchKernelGGL((split_k_kernel<G, 4>), kgrid, kblock, 0, st, a);
-    else hipLaunchKernelGGL((split_k_kernel<G, 8>), kgrid, kblock, 0, st, a);
+    hipLaunchKernelGGL((split_k_kernel<G>), kgrid, kblock, 0, st, a);
     if (hipError_t e = hipGetLastError()) return e;
     if (mid_event)
         if (hipError_t e = hipEventRecord(mid_event, st)) return e;

@@ -17,14 +17,37 @@ struct KShared {
     float new_logit[G];                 // fused append: q . knew, accumulated in channel order
 };
 
-// Rule 1 for the 128 columns of (b, h).  Called by every thread of a workgroup of at least 128 threads
-// (contains barriers); afterwards ks holds q as fp32 and the level masks.
+// Rule 1 for the 128 columns of (b, h), in two steps so that a caller can put other loads in flight between the
+// issue of the loads here and their first use.  Both are called by every thread of a workgroup of at least 128
+// threads (the second contains barriers); afterwards ks holds q as fp32 and the level masks.
 // k_new_bits: fp16 bits of channel tid of a token that is being appended in the same kernel (fused append),
 // else -1: K_colmax then counts that token, and the token's row, read at the column levels, is left in
-// ks.knew for new_token_logit().  Returns the K_colmax of channel tid (tid < 128) that the levels used.
+// ks.knew for new_token_logit().
 template <int G>
-__device__ __forceinline__ uint32_t k_levels(const DecodeArgs& a, int b, int h, KShared<G>& ks, bool export_levels,
-                                             int k_new_bits = -1)
+struct KLevelsIn {
+    uint32_t cm;         // K_colmax of channel tid as stored
+    uint32_t qbits[G];   // fp16 bits of q[g][tid]
+};
+
+template <int G>
+__device__ __forceinline__ void k_levels_load(const DecodeArgs& a, int b, int h, KLevelsIn<G>& in)
+{
+    const int tid = threadIdx.x;
+    const size_t bh = size_t(b) * a.s.Hkv + h;
+    in.cm = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) in.qbits[g] = 0;
+    if (tid < kD) {
+        in.cm = a.colmax[bh * kD + tid];
+#pragma unroll
+        for (int g = 0; g < G; ++g) in.qbits[g] = a.q[(size_t(b) * a.s.Hq + size_t(h) * G + g) * kD + tid];
+    }
+}
+
+// Returns the K_colmax of channel tid (tid < 128) that the levels used.
+template <int G>
+__device__ __forceinline__ uint32_t k_levels_finish(const DecodeArgs& a, int b, int h, KShared<G>& ks, bool export_levels,
+                                                    int k_new_bits, const KLevelsIn<G>& in)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t bh = size_t(b) * a.s.Hkv + h;
@@ -33,14 +56,14 @@ __device__ __forceinline__ uint32_t k_levels(const DecodeArgs& a, int b, int h, 
     float P[G];
     uint32_t colmax_used = 0;
     if (tid < kD) {
-        uint32_t cm = a.colmax[bh * kD + tid];
+        uint32_t cm = in.cm;
         if (k_new_bits >= 0) cm = max(cm, uint32_t(k_new_bits) & 0x7FFFu);
         colmax_used = cm;
         cm = cm < 0x0400u ? 0x0400u : cm;               // below the smallest normal: its places are 2^-14's
         const float cmf = half_bits_to_float(cm);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const float qf = half_bits_to_float(a.q[(size_t(b) * a.s.Hq + size_t(h) * G + g) * kD + tid]);
+            const float qf = half_bits_to_float(in.qbits[g]);
             ks.q[g][tid] = qf;
             P[g] = qf * cmf;                             // exact: 11-bit x 11-bit significands
             if (P[g] != 0.0f) atomicMax(&ks.emax[g], float_exp_field(P[g]));
@@ -72,6 +95,15 @@ __device__ __forceinline__ uint32_t k_levels(const DecodeArgs& a, int b, int h, 
     return colmax_used;
 }
 
+template <int G>
+__device__ __forceinline__ uint32_t k_levels(const DecodeArgs& a, int b, int h, KShared<G>& ks, bool export_levels,
+                                             int k_new_bits = -1)
+{
+    KLevelsIn<G> in;
+    k_levels_load<G>(a, b, h, in);
+    return k_levels_finish<G>(a, b, h, ks, export_levels, k_new_bits, in);
+}
+
 // Fused append: the logit of the token that is being appended, from ks.knew, with the same arithmetic as a
 // tile lane (fp32, channels ascending).  One thread per query head of the group.
 template <int G>
@@ -98,110 +130,133 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v)
     return (uint64_t(hi32) << 32) | uint64_t(lo32);
 }
 
-// One wave, one tile of 64*TPL tokens of (b, h) starting at 256-token block blk0: lane -> TPL consecutive
-// tokens of one block (TPL = 4: the wave reads one contiguous 256-B run of K_hi per channel; TPL = 8: two
-// runs, one per block).  Channels are processed U at a time.
-// If the column's level asks for it the matching runs of K_mid / K_lo are read as well.  Every byte is used
-// by exactly one lane, so nothing is staged through LDS.  The logit of a token is accumulated in fp32 over
-// channels in ascending order (one lane, no reduction).  Logits go to a.logits with cache policy `aux`
-// (kAuxSc1 when another workgroup of the same kernel will read them); the maximum over the tile's valid
-// tokens is returned for every query head of the group (same value in all lanes).
-template <int G, int TPL, int U>
-__device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int blk0, int len, const KShared<G>& ks,
-                                       int aux, float (&tile_max)[G])
+// One wave, one 256-token block blk of (b, h): lane -> tokens 4*lane .. 4*lane+3 of the block; the logit of a token
+// is accumulated in fp32 over channels in ascending order inside its lane (no reduction).
+// Channels are processed 8 at a time.  Per group the wave fetches the 2-KB run of K_hi (8 columns x 256 B,
+// contiguous in the channel-major block) with two 16-B loads per lane, and the 1-KB runs of K_mid / K_lo with one
+// 16-B load per lane each, lane -> (column lane/8, 16 bytes): a column whose level does not ask for a plane is
+// left out by sending its 8 lanes out of range (nothing is fetched, zeros come back).  Four vector-memory
+// instructions per group instead of one per column and plane: the address unit of a CU takes about as long
+// for a 2-byte-per-lane load as for a 16-byte one, and the count of such instructions, not their bytes, bounded
+// this pass.  The loaded registers are in "memory order"; they are written to a 4-KB wave-private LDS
+// area and read back in "token order" (lane -> its 4 tokens of every column).
+// Logits go to a.logits with cache policy `aux` (kAuxSc1 when another workgroup of the same kernel will read
+// them) and are left in acc; the maximum over the tile's valid tokens is returned for every query head of the
+// group (same value in all lanes).
+constexpr int kKU = 8;            // columns per group
+constexpr int kKStage = 4096;     // bytes of LDS staging per wave
+
+// HI bytes of the first two groups of a tile, issued before the levels are known (they are always read):
+// pre[] is handed to k_tile (use_pre = true) for the same block.
+__device__ __forceinline__ void k_tile_pre(const DecodeArgs& a, int b, int h, int blk, u32x4_t (&pre)[4])
 {
-    static_assert(TPL == 4 || TPL == 8, "tokens per lane");
-    static_assert(U == 4 || U == 8, "channels per group");
-    constexpr int kLanesPerBlock = kTB / TPL;
     const int lane = threadIdx.x & 63;
-    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
+    const size_t bh = size_t(b) * a.s.Hkv + h;
+    const __amdgpu_buffer_rsrc_t rh = make_rsrc(a.k_hi + (bh * a.s.Ncap + size_t(blk) * kTB) * kD, uint32_t(kTB) * kD);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pre[i] = buf_load_b128(rh, uint32_t(lane) * 16 + i * 1024);
+}
+
+template <int G>
+__device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int blk, int len, const KShared<G>& ks,
+                                       int aux, float (&tile_max)[G], const u32x4_t (&pre)[4], bool use_pre,
+                                       float (&acc)[G][4], uint8_t* stage)
+{
+    constexpr int U = kKU;
+    const int lane = threadIdx.x & 63;
+    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const size_t bh = size_t(b) * Hkv + h;
+    blk = __builtin_amdgcn_readfirstlane(blk);   // wave-uniform by contract: scalar addressing
 
-    const int blk = blk0 + lane / kLanesPerBlock;
-    const bool live = blk < NB;                          // Ncap may end inside the tile
-    const int blk_ld = live ? blk : NB - 1;              // such lanes re-read the last block and store nothing
-    const int j0 = (lane % kLanesPerBlock) * TPL;
-    const uint32_t off_hi = uint32_t(blk_ld) * kD * kTB + j0;
-    const uint32_t off_nib = uint32_t(blk_ld) * kD * (kTB / 2) + j0 / 2;
-
-    float acc[G][TPL];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int i = 0; i < TPL; ++i) acc[g][i] = 0.0f;
+        for (int i = 0; i < 4; ++i) acc[g][i] = 0.0f;
 
     // the level masks live in scalar registers for the whole loop
     const uint64_t nm0 = uniform64(ks.need_mid[0]), nm1 = uniform64(ks.need_mid[1]);
     const uint64_t nl0 = uniform64(ks.need_lo[0]), nl1 = uniform64(ks.need_lo[1]);
-
-    struct Group {
-        uint32_t h0[U], h1[U];   // HI bytes of tokens 0..3 / 4..7 (h1 unused for TPL = 4)
-        uint32_t m[U], l[U];     // MID / LO nibbles, token 2i in the low nibble of byte i
-    };
-    // bits of the U channels starting at d0 (d0 % U == 0, so a group never straddles the two words)
+    // bits of the U columns starting at d0 (d0 % U == 0, so a group never straddles the two words)
     auto bits_at = [&](uint64_t w0, uint64_t w1, int d0) -> uint32_t {
         return d0 < kD ? (uint32_t)((d0 < 64 ? w0 : w1) >> (d0 & 63)) & ((1u << U) - 1) : 0u;
     };
-    // A plane that a column does not need is read through a descriptor of size zero: the range check then
-    // answers every lane with zero and nothing is fetched.  The choice is scalar (the level is per column),
-    // the per-lane offset is the same register for every load, the channel goes into the scalar offset.
-    const uint32_t slab = uint32_t(Ncap) * (kD / 2);
-    auto issue = [&](Group& gr, int d0) {
+    const uint8_t* hi_blk = a.k_hi + (bh * Ncap + size_t(blk) * kTB) * kD;
+    const uint8_t* mid_blk = a.k_mid + (bh * Ncap + size_t(blk) * kTB) * (kD / 2);
+    const uint8_t* lo_blk = a.k_lo + (bh * Ncap + size_t(blk) * kTB) * (kD / 2);
+    const uint32_t voff = uint32_t(lane) * 16;
+    const uint32_t col = uint32_t(lane) >> 3;   // the column of the group this lane fetches nibbles of
+
+    struct Group {
+        u32x4_t h0, h1;   // bytes 16*lane .. +15 of the first / second KB of the HI run (columns 0..3 / 4..7)
+        u32x4_t m, l;     // bytes 16*lane .. +15 of the MID / LO run (column lane/8)
+    };
+    // groups past the last column are issued through descriptors of size zero: nothing is fetched
+    auto issue_hi = [&](Group& gr, int d0) {
+        const __amdgpu_buffer_rsrc_t rh = make_rsrc(hi_blk, d0 < kD ? uint32_t(kTB) * kD : 0u);
+        gr.h0 = __builtin_amdgcn_raw_buffer_load_b128(rh, voff, d0 * kTB, 0);
+        gr.h1 = __builtin_amdgcn_raw_buffer_load_b128(rh, voff + 1024, d0 * kTB, 0);
+    };
+    auto issue_nib = [&](Group& gr, int d0) {
         const uint32_t bm = bits_at(nm0, nm1, d0), bl = bits_at(nl0, nl1, d0);
-        const __amdgpu_buffer_rsrc_t rh = make_rsrc(a.k_hi + bh * Ncap * kD, d0 < kD ? 2 * slab : 0u);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const __amdgpu_buffer_rsrc_t rm = make_rsrc(a.k_mid + bh * Ncap * (kD / 2), ((bm >> u) & 1u) ? slab : 0u);
-            const __amdgpu_buffer_rsrc_t rl = make_rsrc(a.k_lo + bh * Ncap * (kD / 2), ((bl >> u) & 1u) ? slab : 0u);
-            if constexpr (TPL == 8) {
-                const u32x2_t hh = __builtin_amdgcn_raw_buffer_load_b64(rh, off_hi + u * kTB, d0 * kTB, 0);
-                gr.h0[u] = hh.x;
-                gr.h1[u] = hh.y;
-                gr.m[u] = __builtin_amdgcn_raw_buffer_load_b32(rm, off_nib + u * (kTB / 2), d0 * (kTB / 2), 0);
-                gr.l[u] = __builtin_amdgcn_raw_buffer_load_b32(rl, off_nib + u * (kTB / 2), d0 * (kTB / 2), 0);
-            } else {
-                gr.h0[u] = __builtin_amdgcn_raw_buffer_load_b32(rh, off_hi + u * kTB, d0 * kTB, 0);
-                gr.m[u] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rm, off_nib + u * (kTB / 2), d0 * (kTB / 2), 0);
-                gr.l[u] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rl, off_nib + u * (kTB / 2), d0 * (kTB / 2), 0);
-            }
-        }
+        const uint32_t size = d0 < kD ? uint32_t(kTB) * (kD / 2) : 0u;
+        const __amdgpu_buffer_rsrc_t rm = make_rsrc(mid_blk, size), rl = make_rsrc(lo_blk, size);
+        const uint32_t base = voff + uint32_t(d0 < kD ? d0 : 0) * (kTB / 2);
+        gr.m = __builtin_amdgcn_raw_buffer_load_b128(rm, ((bm >> col) & 1u) ? base : kSkip, 0, 0);
+        gr.l = __builtin_amdgcn_raw_buffer_load_b128(rl, ((bl >> col) & 1u) ? base : kSkip, 0, 0);
+    };
+    auto issue = [&](Group& gr, int d0) {
+        issue_hi(gr, d0);
+        issue_nib(gr, d0);
     };
     auto compute = [&](const Group& gr, int d0) {
         const uint32_t bm = bits_at(nm0, nm1, d0), bl = bits_at(nl0, nl1, d0);
+        // memory order -> token order through the wave's LDS area (LDS serves a wave's accesses in order)
+        __builtin_amdgcn_wave_barrier();
+        *reinterpret_cast<u32x4_t*>(stage + voff) = gr.h0;
+        *reinterpret_cast<u32x4_t*>(stage + 1024 + voff) = gr.h1;
+        *reinterpret_cast<u32x4_t*>(stage + 2048 + voff) = gr.m;
+        *reinterpret_cast<u32x4_t*>(stage + 3072 + voff) = gr.l;
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            uint32_t ev, od;   // low bytes of tokens 0,2,4,6 / 1,3,5,7
+            const uint32_t hh = *reinterpret_cast<const uint32_t*>(stage + u * kTB + lane * 4);
+            const uint32_t mm = *reinterpret_cast<const uint16_t*>(stage + 2048 + u * (kTB / 2) + lane * 2);
+            const uint32_t ll = *reinterpret_cast<const uint16_t*>(stage + 3072 + u * (kTB / 2) + lane * 2);
+            uint32_t ev, od;   // low bytes of tokens 0,2 / 1,3
             if ((bl >> u) & 1u) {   // all 16 bits read (uniform branch)
-                ev = ((gr.m[u] << 4) & 0xF0F0F0F0u) | (gr.l[u] & 0x0F0F0F0Fu);
-                od = (gr.m[u] & 0xF0F0F0F0u) | ((gr.l[u] >> 4) & 0x0F0F0F0Fu);
+                ev = ((mm << 4) & 0xF0F0F0F0u) | (ll & 0x0F0F0F0Fu);
+                od = (mm & 0xF0F0F0F0u) | ((ll >> 4) & 0x0F0F0F0Fu);
             } else {                // 12 bits (MID read, fill 1000) or 8 bits (MID word is zero, fill 1000 0000)
                 const uint32_t fill = ((bm >> u) & 1u) ? 0x08080808u : 0x80808080u;
-                ev = ((gr.m[u] << 4) & 0xF0F0F0F0u) | fill;
-                od = (gr.m[u] & 0xF0F0F0F0u) | fill;
+                ev = ((mm << 4) & 0xF0F0F0F0u) | fill;
+                od = (mm & 0xF0F0F0F0u) | fill;
             }
-            float k[TPL];
-            const uint32_t p0 = __builtin_amdgcn_perm(gr.h0[u], ev, 0x06010400u);   // tokens (0,2)
-            const uint32_t p1 = __builtin_amdgcn_perm(gr.h0[u], od, 0x07010500u);   // tokens (1,3)
-            k[0] = lo_half(p0); k[2] = hi_half(p0); k[1] = lo_half(p1); k[3] = hi_half(p1);
-            if constexpr (TPL == 8) {
-                const uint32_t p2 = __builtin_amdgcn_perm(gr.h1[u], ev, 0x06030402u);   // tokens (4,6)
-                const uint32_t p3 = __builtin_amdgcn_perm(gr.h1[u], od, 0x07030502u);   // tokens (5,7)
-                k[4] = lo_half(p2); k[6] = hi_half(p2); k[5] = lo_half(p3); k[7] = hi_half(p3);
-            }
+            const uint32_t p0 = __builtin_amdgcn_perm(hh, ev, 0x06010400u);   // tokens (0,2)
+            const uint32_t p1 = __builtin_amdgcn_perm(hh, od, 0x07010500u);   // tokens (1,3)
+            const float k[4] = {lo_half(p0), lo_half(p1), hi_half(p0), hi_half(p1)};
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float qd = ks.q[g][d0 + u];
                 // q*k is exact in fp32, so the fused form rounds exactly like multiply-then-add
 #pragma unroll
-                for (int i = 0; i < TPL; ++i) acc[g][i] = fmaf(qd, k[i], acc[g][i]);
+                for (int i = 0; i < 4; ++i) acc[g][i] = fmaf(qd, k[i], acc[g][i]);
             }
         }
+        __builtin_amdgcn_wave_barrier();
     };
-    // three groups rotate by name: two are in flight while one is consumed (48 loads outstanding at most,
-    // below the 6-bit counter of outstanding vector-memory operations)
+    // three groups rotate by name: two are in flight (8 KB per wave) while one is consumed
     Group A, B, C;
-    issue(A, 0);
-    issue(B, U);
+    if (use_pre) {   // uniform: the HI bytes of the first two groups are already in flight (k_tile_pre)
+        A.h0 = pre[0];
+        A.h1 = pre[1];
+        B.h0 = pre[2];
+        B.h1 = pre[3];
+        issue_nib(A, 0);
+        issue_nib(B, U);
+    } else {
+        issue(A, 0);
+        issue(B, U);
+    }
 #pragma unroll 1
     for (int d0 = 0; d0 < kD; d0 += 3 * U) {
         issue(C, d0 + 2 * U);
@@ -213,24 +268,20 @@ __device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int bl
     }
 
     // ---- logits out, tile maxima -----------------------------------------------------------------
-    const int t0 = blk * kTB + j0;
+    const int t0 = blk * kTB + lane * 4;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
         const __amdgpu_buffer_rsrc_t rs_lg = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
-#pragma unroll
-        for (int i = 0; i < TPL; i += 4) {
-            u32x4_t w;
-            w.x = float_bits(acc[g][i]); w.y = float_bits(acc[g][i + 1]);
-            w.z = float_bits(acc[g][i + 2]); w.w = float_bits(acc[g][i + 3]);
-            const uint32_t off = live ? uint32_t(t0 + i) * 4u : kSkip;   // out of range: the store is dropped
-            if (aux) __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, off, 0, kAuxSc1);
-            else __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, off, 0, 0);
-        }
+        u32x4_t w;
+        w.x = float_bits(acc[g][0]); w.y = float_bits(acc[g][1]);
+        w.z = float_bits(acc[g][2]); w.w = float_bits(acc[g][3]);
+        if (aux) __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, uint32_t(t0) * 4u, 0, kAuxSc1);
+        else __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, uint32_t(t0) * 4u, 0, 0);
         float m = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < TPL; ++i)
-            if (live && t0 + i < len) m = fmaxf(m, acc[g][i]);
+        for (int i = 0; i < 4; ++i)
+            if (t0 + i < len) m = fmaxf(m, acc[g][i]);
         tile_max[g] = wave_max(m);
     }
 }

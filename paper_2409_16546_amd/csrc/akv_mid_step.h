@@ -13,22 +13,28 @@ constexpr int kMidMaxWaves = 16;
 struct MidShared {
     float M[kMaxG];              // in: global max logit of every query head of the group (set by the caller)
     int ehat[kD];                // out: result exponent per channel, min over the group
-    int cnt[kBuckets];
+    int cnt[kBuckets];           // histogram of score exponents (several chunks of tokens per thread)
+    int cntw[kMidMaxWaves][kBuckets + 1];   // ... per wave (one chunk: every thread owns four tokens)
     int wlt[kMidMaxWaves], weq[kMidMaxWaves];
     int sel[AKV_MAX_TOPK];
-    float phat[AKV_MAX_TOPK];
-    uint16_t v[AKV_MAX_TOPK][kD];
-    int J, fromcut;
+    alignas(16) float phat[AKV_MAX_TOPK];
+    alignas(16) uint32_t v2[AKV_MAX_TOPK / 2][kD];   // fp16 bits of the selected V rows: rows 2i (low half) and 2i+1 of channel d
 };
 
 // Run by one workgroup of NT threads for one (sequence b, KV head h) of len tokens, after every logit of the pair is
 // visible to it and sm.M holds the global max logit of each query head; the G query heads of the group are
 // handled one after another.  CROSS: the logits were written by other workgroups of the same kernel and are
-// read at device scope.  Logits are walked 4*NT at a time (a float4 per thread); the selected V rows are
-// fetched by all threads at once into LDS so that O_est costs one memory latency, then each channel runs its
-// ordered FMA chain.  Results: a.M, a.Ehat (global, for a later kernel) and sm.ehat (LDS).
+// read at device scope.
+// use_own: own[g][i] is the logit of token 4*tid + i of query head g (the caller still has them in registers);
+// only used when the sequence fits one chunk of 4*NT tokens.
+// Token order is (thread, i) inside a chunk of 4*NT tokens, chunks ascending.  One chunk (the common case):
+// per-wave histograms give every wave the cut bucket and the number of selected tokens in the waves before it
+// without a second barrier; ballots order the tokens inside the wave.  The selected V rows are fetched by all
+// threads at once into LDS so that O_est costs one memory latency, then each channel runs its ordered FMA chain
+// from operands fetched up front.  Results: a.M, a.Ehat (global, for a later kernel) and sm.ehat (LDS).
 template <int G, int NT, bool CROSS>
-__device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int len, MidShared& sm)
+__device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int len, MidShared& sm,
+                                         const float (&own)[G][4], bool use_own)
 {
     constexpr int kWaves = NT / 64;
     constexpr int kChunk = NT * 4;
@@ -38,14 +44,12 @@ __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int 
     int (&weq_s)[kMidMaxWaves] = sm.weq;
     int (&sel_s)[AKV_MAX_TOPK] = sm.sel;
     float (&phat_s)[AKV_MAX_TOPK] = sm.phat;
-    uint16_t (&v_s)[AKV_MAX_TOPK][kD] = sm.v;
-    int& J_s = sm.J;
-    int& fromcut_s = sm.fromcut;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const size_t bh = size_t(b) * Hkv + h;
     int ehat = 32767;   // min over the group of the result exponent of channel tid (tid < D)
+    const bool one_chunk = len <= kChunk;   // uniform
 
     for (int g = 0; g < G; ++g) {
         const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
@@ -60,97 +64,171 @@ __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int 
             continue;
         }
         const float M = sm.M[g];
-        if (tid < kBuckets) cnt_s[tid] = 0;
-        __syncthreads();
-
-        // ---- histogram of score exponents: bucket j = -a_t, 0..64 -------------------------------------
-        for (int t0 = tid * 4; t0 < len; t0 += kChunk) {
-            const float4 l4 = load4(t0);
-            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+        const int kk = a.topk < len ? a.topk : len;
+        // score exponents of four tokens: x, and the bucket j = -a_t (1000 for tokens at or past len)
+        auto score4 = [&](int t0, const float (&lv)[4], float (&x)[4], int (&j)[4]) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                if (t0 + i < len) {
-                    const int at = score_a(score_x(lv[i], M, a.c));
-                    atomicAdd(&cnt_s[-at], 1);
-                    if (a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)at;
-                }
+                x[i] = score_x(lv[i], M, a.c);
+                j[i] = t0 + i < len ? -score_a(x[i]) : 1000;
             }
-        }
-        __syncthreads();
-        const int kk = a.topk < len ? a.topk : len;
-        if (tid == 0) {
-            int J = 0, below = 0;   // below = tokens in buckets < J
-            while (below + cnt_s[J] < kk) below += cnt_s[J++];
-            J_s = J;
-            fromcut_s = kk - below;
-        }
-        __syncthreads();
-        const int J = J_s, fromcut = fromcut_s;
-
-        // ---- ordered selection: every token above the cut bucket, the first `fromcut` of the cut bucket --
-        int tot_lt = 0, tot_eq = 0;   // tokens of each kind before the current chunk (same in all threads)
-        for (int c0 = 0; c0 < len; c0 += kChunk) {
-            const int t0 = c0 + tid * 4;
-            float x[4];
-            int j[4];
-            int c_lt = 0, c_eq = 0;
+        };
+        auto load_score4 = [&](int t0, float (&x)[4], int (&j)[4]) {
+            float lv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
             if (t0 < len) {
                 const float4 l4 = load4(t0);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    x[i] = score_x(lv[i], M, a.c);
-                    j[i] = t0 + i < len ? -score_a(x[i]) : 1000;
-                    c_lt += j[i] < J;
-                    c_eq += j[i] == J;
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    x[i] = 0.0f;
-                    j[i] = 1000;
-                }
+                lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w;
             }
-            int s_lt = c_lt, s_eq = c_eq;   // inclusive scan over the lanes of the wave
+            score4(t0, lv, x, j);
+        };
+        // position pos of a selected token: its index and piecewise-linear weight go to LDS
+        auto emit = [&](int pos, int t, float x, int j) {
+            const float fl = floorf(x);
+            const float f = x - fl;
+            sel_s[pos] = t;
+            phat_s[pos] = ldexpf(1.0f + f, -j);   // 2^x with a linear mantissa, the exponent floored at -64
+        };
+        // tokens of each kind in lower lanes of the wave (token order = lane, then i), and in the whole wave
+        auto wave_order = [&](const int (&j)[4], int J, int& n_lt, int& n_eq, int& w_lt, int& w_eq) {
+            n_lt = n_eq = w_lt = w_eq = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint64_t b_lt = __ballot(j[i] < J), b_eq = __ballot(j[i] == J);
+                n_lt += __builtin_amdgcn_mbcnt_hi((uint32_t)(b_lt >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b_lt, 0));
+                n_eq += __builtin_amdgcn_mbcnt_hi((uint32_t)(b_eq >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b_eq, 0));
+                w_lt += __builtin_popcountll(b_lt);
+                w_eq += __builtin_popcountll(b_eq);
+            }
+        };
+        // the cut from bucket totals (lane l holds bucket l, c64 is bucket 64): first bucket J where the running
+        // count reaches k', and the number of tokens in buckets below it
+        auto find_cut = [&](int c, int& J, int& below) {
+            int incl = c;
             for (int o = 1; o < 64; o <<= 1) {
-                const int u_lt = __shfl_up(s_lt, o), u_eq = __shfl_up(s_eq, o);
-                if (lane >= o) {
-                    s_lt += u_lt;
-                    s_eq += u_eq;
-                }
+                const int u = __shfl_up(incl, o);
+                if (lane >= o) incl += u;
             }
-            if (lane == 63) {
-                wlt_s[wave] = s_lt;
-                weq_s[wave] = s_eq;
+            const uint64_t reached = __ballot(incl >= kk);
+            J = reached ? __builtin_ctzll(reached) : 64;   // bucket 64 is the cut only if none before it is
+            below = J == 0 ? 0 : __shfl(incl, J - 1);
+        };
+
+        if (one_chunk) {
+            // ---- per-wave histograms of score exponents: bucket j = -a_t, 0..64 -------------------------
+            for (int idx = tid; idx < kWaves * (kBuckets + 1); idx += NT) (&sm.cntw[0][0])[idx] = 0;
+            float x[4];
+            int j[4];
+            const int t0 = tid * 4;
+            if (use_own) {
+                float lv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int gg = 0; gg < G; ++gg)   // static indices keep the caller's array in registers
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) lv[i] = gg == g ? own[gg][i] : lv[i];
+                score4(t0, lv, x, j);
+            } else {
+                load_score4(t0, x, j);
             }
             __syncthreads();
-            int n_lt = tot_lt + s_lt - c_lt, n_eq = tot_eq + s_eq - c_eq;   // tokens of each kind before this thread's four
-            int chunk_lt = 0, chunk_eq = 0;
-            for (int w = 0; w < kWaves; ++w) {
-                if (w < wave) {
-                    n_lt += wlt_s[w];
-                    n_eq += weq_s[w];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (j[i] <= 64) {
+                    atomicAdd(&sm.cntw[wave][j[i]], 1);
+                    if (a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[i]);
                 }
-                chunk_lt += wlt_s[w];
-                chunk_eq += weq_s[w];
             }
+            __syncthreads();
+            // ---- the cut, and what the waves before this one hold, from the histograms -------------------
+            int tot = 0, before = 0;   // bucket `lane`: all waves / the waves before this one
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const int c = sm.cntw[w][lane];
+                tot += c;
+                before += w < wave ? c : 0;
+            }
+            int J, below;
+            find_cut(tot, J, below);
+            const int fromcut = kk - below;
+            int base_lt = lane < J ? before : 0;   // selected-for-sure tokens in earlier waves: buckets < J
+            for (int o = 1; o < 64; o <<= 1) base_lt += __shfl_xor(base_lt, o);
+            int base_eq;                            // tokens of the cut bucket in earlier waves
+            if (J < 64) {
+                base_eq = __shfl(before, J);
+            } else {
+                base_eq = 0;
+                for (int w = 0; w < wave; ++w) base_eq += sm.cntw[w][64];
+            }
+            // ---- ordered selection: every token above the cut bucket, the first `fromcut` of the cut bucket --
+            int n_lt, n_eq, w_lt, w_eq;
+            wave_order(j, J, n_lt, n_eq, w_lt, w_eq);
+            n_lt += base_lt;
+            n_eq += base_eq;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const bool is_lt = j[i] < J, is_eq = j[i] == J;
-                if (is_lt || (is_eq && n_eq < fromcut)) {
-                    const int pos = n_lt + (n_eq < fromcut ? n_eq : fromcut);
-                    const float fl = floorf(x[i]);
-                    const float f = x[i] - fl;
-                    sel_s[pos] = t0 + i;
-                    phat_s[pos] = ldexpf(1.0f + f, -j[i]);   // piecewise-linear 2^x with the exponent floored at -64
-                }
+                if (is_lt || (is_eq && n_eq < fromcut)) emit(n_lt + (n_eq < fromcut ? n_eq : fromcut), t0 + i, x[i], j[i]);
                 n_lt += is_lt;
                 n_eq += is_eq;
             }
-            tot_lt += chunk_lt;
-            tot_eq += chunk_eq;
+        } else {
+            // ---- histogram of score exponents over all chunks -----------------------------------------
+            if (tid < kBuckets) cnt_s[tid] = 0;
             __syncthreads();
-            if (tot_lt + (tot_eq < fromcut ? tot_eq : fromcut) >= kk) break;   // uniform
+            for (int t0 = tid * 4; t0 < len; t0 += kChunk) {
+                float x[4];
+                int j[4];
+                load_score4(t0, x, j);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (j[i] <= 64) {
+                        atomicAdd(&cnt_s[j[i]], 1);
+                        if (a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[i]);
+                    }
+                }
+            }
+            __syncthreads();
+            int J, below;
+            find_cut(cnt_s[lane], J, below);
+            const int fromcut = kk - below;
+            // ---- ordered selection, chunk by chunk --------------------------------------------------------
+            int tot_lt = 0, tot_eq = 0;   // tokens of each kind before the current chunk (same in all threads)
+            for (int c0 = 0; c0 < len; c0 += kChunk) {
+                const int t0 = c0 + tid * 4;
+                float x[4];
+                int j[4];
+                load_score4(t0, x, j);
+                int n_lt, n_eq, w_lt, w_eq;
+                wave_order(j, J, n_lt, n_eq, w_lt, w_eq);
+                if (lane == 0) {
+                    wlt_s[wave] = w_lt;
+                    weq_s[wave] = w_eq;
+                }
+                __syncthreads();
+                n_lt += tot_lt;
+                n_eq += tot_eq;
+                int chunk_lt = 0, chunk_eq = 0;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    const int a_lt = wlt_s[w], a_eq = weq_s[w];
+                    if (w < wave) {
+                        n_lt += a_lt;
+                        n_eq += a_eq;
+                    }
+                    chunk_lt += a_lt;
+                    chunk_eq += a_eq;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool is_lt = j[i] < J, is_eq = j[i] == J;
+                    if (is_lt || (is_eq && n_eq < fromcut)) emit(n_lt + (n_eq < fromcut ? n_eq : fromcut), t0 + i, x[i], j[i]);
+                    n_lt += is_lt;
+                    n_eq += is_eq;
+                }
+                tot_lt += chunk_lt;
+                tot_eq += chunk_eq;
+                __syncthreads();
+                if (tot_lt + (tot_eq < fromcut ? tot_eq : fromcut) >= kk) break;   // uniform
+            }
         }
         __syncthreads();
 
@@ -164,16 +242,16 @@ __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int 
             uint32_t pa[4], pb[4];
             assemble8(hi.x, hi.y, mid.x, lo.x, pa);
             assemble8(hi.z, hi.w, mid.y, lo.y, pb);
-            uint16_t* dst = &v_s[row][cl * 16];
+            uint16_t* dst = reinterpret_cast<uint16_t*>(&sm.v2[row >> 1][cl * 16]) + (row & 1);   // element stride: 2 halves
             const uint32_t pp[8] = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], pb[2], pb[3]};
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {   // pairs (0,2),(1,3) then (4,6),(5,7) of each eight
                 const uint32_t e = pp[2 * q4], o = pp[2 * q4 + 1];
                 const int base = (q4 >> 1) * 8 + (q4 & 1) * 4;
-                dst[base + 0] = (uint16_t)e;
-                dst[base + 1] = (uint16_t)o;
-                dst[base + 2] = (uint16_t)(e >> 16);
-                dst[base + 3] = (uint16_t)(o >> 16);
+                dst[2 * (base + 0)] = (uint16_t)e;
+                dst[2 * (base + 1)] = (uint16_t)o;
+                dst[2 * (base + 2)] = (uint16_t)(e >> 16);
+                dst[2 * (base + 3)] = (uint16_t)(o >> 16);
             }
         }
         __syncthreads();
@@ -182,7 +260,22 @@ __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int 
         if (tid < kD) {
             const int d = tid;
             float acc = 0.0f;
-            for (int i = 0; i < kk; ++i) acc = fmaf(phat_s[i], half_bits_to_float(v_s[i][d]), acc);
+            for (int i0 = 0; i0 < kk; i0 += 16) {   // operands fetched 16 rows at a time, the additions stay in selection order
+                float pv[16];
+                uint32_t vv[8];
+#pragma unroll
+                for (int i = 0; i < 16; i += 4) {
+                    const float4 p4 = *reinterpret_cast<const float4*>(&phat_s[i0 + i]);
+                    pv[i] = p4.x; pv[i + 1] = p4.y; pv[i + 2] = p4.z; pv[i + 3] = p4.w;
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) vv[i] = sm.v2[(i0 >> 1) + i][d];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (i0 + 2 * i < kk) acc = fmaf(pv[2 * i], lo_half(vv[i]), acc);
+                    if (i0 + 2 * i + 1 < kk) acc = fmaf(pv[2 * i + 1], hi_half(vv[i]), acc);
+                }
+            }
             const int E = float_exp_field(acc) - 127;
             ehat = E < ehat ? E : ehat;
             if (a.dbg.oest) a.dbg.oest[hq * kD + d] = acc;

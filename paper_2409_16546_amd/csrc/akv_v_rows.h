@@ -9,185 +9,262 @@ namespace akv {
 
 // Byte-parallel form of Rule 2 for one token row.  With w_d = guard - 5 - Ehat_d and s = Ahat_t the
 // mantissa bits element (t,d) needs are m = ev' + w_d + s (ev' = max(exponent field, 1)); the row is read
-// at level >= 1 iff some m >= 3 and at level 2 iff some m >= 7.  Per byte: ev + B + (s + 64) with
-// B1_d = clamp(w_d + 61, 0, 128), B2_d = clamp(w_d + 57, 0, 128) sets bit 7 exactly when ev + w_d + s
-// reaches 3 resp. 7 (no carry: the sum is at most 31 + 128 + 64); the clamps only cut cases that are
-// decided for every ev in 0..31 and s in -64..0.  ev' differs from ev only for ev = 0, which adds the
-// row-independent test 1 + max_d w_d + s >= 3 (resp. 7).
-__device__ __forceinline__ uint32_t clamp_byte(int v) { return (uint32_t)(v < 0 ? 0 : (v > 128 ? 128 : v)); }
+// at level >= 1 iff some m >= 3 and at level 2 iff some m >= 7.  Per byte: S = ev + B_d + (s + 64) with
+// B_d = clamp(w_d + 61, 4, 132) reaches 128 exactly when ev + w_d + s reaches 3, and 132 exactly when it
+// reaches 7: bit 7 of S and bit 7 of S - 4 are the two answers (no carry and no borrow: 4 <= S <= 227).
+// The clamps only cut cases that are decided for every ev in 0..31 and s in -64..0.  ev' differs from ev
+// only for ev = 0, which adds the row-independent test 1 + max_d w_d + s >= 3 (resp. 7).
+__device__ __forceinline__ uint32_t clamp_byte(int v) { return (uint32_t)(v < 4 ? 4 : (v > 132 ? 132 : v)); }
 
 // Per-lane constants of Rule 2 for the lane's 16 channels (lane -> channel slice 16 * (lane % 8))
 struct VRule {
-    uint32_t B1[4], B2[4];
+    uint32_t B[4];
     int ehat[16];   // only read by the variant that exports per-element needs
     int wmax;       // max over all 128 channels of w_d
+    int force;      // -1, or the level every row is read at (then B = 4: no byte ever reaches bit 7)
 };
 
 // ehat: the 128 result exponents of the KV head (global memory or LDS)
-__device__ __forceinline__ void v_rule_setup(const int* ehat, int guard_bits, VRule& vr)
+__device__ __forceinline__ void v_rule_setup(const int* ehat, int guard_bits, int force_level, VRule& vr)
 {
     const int cl = threadIdx.x & 7;
     int wmax = -100000;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        vr.B1[i] = 0;
-        vr.B2[i] = 0;
+        vr.B[i] = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int e = ehat[cl * 16 + i * 4 + k];
             vr.ehat[i * 4 + k] = e;
             const int w = guard_bits - 5 - e;
             wmax = w > wmax ? w : wmax;
-            vr.B1[i] |= clamp_byte(w + 61) << (8 * k);
-            vr.B2[i] |= clamp_byte(w + 57) << (8 * k);
+            vr.B[i] |= clamp_byte(w + 61) << (8 * k);
         }
+        if (force_level >= 0) vr.B[i] = 0x04040404u;
     }
     for (int o = 1; o < 8; o <<= 1) {
         const int other = __shfl_xor(wmax, o);
         wmax = other > wmax ? other : wmax;
     }
     vr.wmax = wmax;
+    vr.force = force_level;
 }
 
-// One wave walks token rows of (b, h) in batches of 32 (4 groups of 8 rows; lane -> row lane/8 of the group
-// and the 16-channel slice lane%8): batch i covers rows t_first + i*batch_stride .. +31, i < nbatches.  Per
-// batch: decide the 32 rows from their HI bytes, issue the MID / LO loads of the rows that need them, issue
-// the HI loads of the next batch, and only then do the multiply-adds, so that the dependent MID / LO fetch and
-// the next HI fetch are both in flight behind the arithmetic.  Rows at or past len contribute nothing.
-// acc / z accumulate sum_t p_t * v~_td and sum_t p_t per lane (to be reduced over the 8 row lanes, then over
-// waves, by the caller).
-template <int G, bool DEBUG>
+// OR over the 8 lanes of a row (lanes 8r .. 8r+7), result in all of them: two exchanges inside the quads,
+// one with the mirrored lane of the 8-lane half row.
+__device__ __forceinline__ uint32_t or_over_row(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    return v;
+}
+
+// HI bytes of the first batch of a wave, issued early by a caller that has idle time before the V side can
+// start (they depend on nothing but the row range).  Rows at or past len are not fetched.
+template <int KG>
+__device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h, int t_first, int len, u32x4_t (&hi)[KG])
+{
+    const int lane = threadIdx.x & 63;
+    const size_t bh = size_t(b) * a.s.Hkv + h;
+    const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.v_hi + bh * a.s.Ncap * kD, uint32_t(len) * kD);
+    const uint32_t voff = uint32_t(t_first) * kD + uint32_t(lane >> 3) * kD + uint32_t(lane & 7) * 16;
+#pragma unroll
+    for (int gr = 0; gr < KG; ++gr) hi[gr] = buf_load_b128(rs_hi, voff + gr * 8 * kD);
+}
+
+// One wave walks token rows of (b, h) in batches of 8*KG rows (KG groups of 8 rows; lane -> row lane/8 of the
+// group and the 16-channel slice lane%8): batch i covers rows t_first + i*batch_stride .. + 8*KG - 1,
+// i < nbatches.  Three stages per batch, software-pipelined over three named buffers:
+//   L  issue the HI loads and the logit loads (lane j < 8*KG holds the logit of row j of the batch);
+//   D  softmax weight and score exponent once per row, handed to the 8 lanes of the row by lane permutes;
+//      Rule 2 on the HI bytes; MID / LO loads of the rows that need them (the others are issued out of
+//      range: nothing is fetched);
+//   F  assemble the fp16 values, multiply-adds.
+// Iteration i runs L(i+2), D(i+1), F(i): every load has a whole iteration of arithmetic to arrive.
+// The descriptors end at row len, so rows at or past len read as zero without any per-lane test; their weight
+// is forced to zero.  acc accumulates sum_t p_t * v~_td per lane (to be reduced over the 8 row lanes, then
+// over waves, by the caller); z accumulates sum_t p_t per lane (to be summed over all 64 lanes).
+// PRE: pre holds the HI bytes of batch 0 (v_prefetch_hi) if pre_ok.
+template <int G, int KG, bool DEBUG, bool PRE = false>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
                                        int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
-                                       float (&z)[G])
+                                       float (&z)[G], const u32x4_t (&pre)[KG], bool pre_ok)
 {
-    constexpr int kGroups = 4;   // row groups (of 8 rows) per batch
+    constexpr int RB = 8 * KG;
+    // wave-uniform by contract: scalar registers, scalar loop control
+    nbatches = __builtin_amdgcn_readfirstlane(nbatches);
+    t_first = __builtin_amdgcn_readfirstlane(t_first);
+    if (nbatches <= 0) return;
     const int lane = threadIdx.x & 63;
     const int r = lane >> 3, cl = lane & 7;
+    const int jj = lane % RB;                      // row of the batch whose score this lane computes
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const size_t bh = size_t(b) * Hkv + h;
 
     __amdgpu_buffer_rsrc_t rs_lg[G];
 #pragma unroll
     for (int g = 0; g < G; ++g)
-        rs_lg[g] = make_rsrc(a.logits + (size_t(b) * Hq + size_t(h) * G + g) * Ncap, uint32_t(Ncap) * 4u);
-    const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.v_hi + bh * Ncap * kD, uint32_t(Ncap) * kD);
-    const __amdgpu_buffer_rsrc_t rs_mid = make_rsrc(a.v_mid + bh * Ncap * (kD / 2), uint32_t(Ncap) * (kD / 2));
-    const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(a.v_lo + bh * Ncap * (kD / 2), uint32_t(Ncap) * (kD / 2));
+        rs_lg[g] = make_rsrc(a.logits + (size_t(b) * Hq + size_t(h) * G + g) * Ncap, uint32_t(len) * 4u);
+    const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.v_hi + bh * Ncap * kD, uint32_t(len) * kD);
+    const __amdgpu_buffer_rsrc_t rs_mid = make_rsrc(a.v_mid + bh * Ncap * (kD / 2), uint32_t(len) * (kD / 2));
+    const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(a.v_lo + bh * Ncap * (kD / 2), uint32_t(len) * (kD / 2));
+    const uint32_t voff_hi = uint32_t(r) * kD + uint32_t(cl) * 16;
+    const uint32_t voff_nib = uint32_t(r) * (kD / 2) + uint32_t(cl) * 8;
+    const uint32_t voff_lg = uint32_t(jj) * 4;
+    int src[KG];                                   // byte address of lane gr*8 + r for the lane permutes
+#pragma unroll
+    for (int gr = 0; gr < KG; ++gr) src[gr] = (gr * 8 + r) * 4;
 
-    u32x4_t hc[kGroups], hn[kGroups];       // HI bytes of the current / the next batch
-    float lc[kGroups][G], ln[kGroups][G];   // logits of the current / the next batch
-    auto load_batch = [&](int bt, u32x4_t (&hh)[kGroups], float (&ll)[kGroups][G]) {
-#pragma unroll
-        for (int gr = 0; gr < kGroups; ++gr) {
-            const int t = t_first + bt * batch_stride + gr * 8 + r;
-            const bool valid = t < len && bt < nbatches;   // past the wave's rows: nothing is fetched
-            hh[gr] = buf_load_b128(rs_hi, valid ? uint32_t(t) * kD + cl * 16 : kSkip);
-#pragma unroll
-            for (int g = 0; g < G; ++g) ll[gr][g] = bits_float(buf_load_b32(rs_lg[g], valid ? uint32_t(t) * 4u : kSkip));
-        }
+    struct Batch {
+        u32x4_t hi[KG];
+        float lg[G];
+        u32x2_t mid[KG], lo[KG];
+        float p[KG][G];
+        uint32_t fill[KG];
     };
-    load_batch(0, hc, lc);
-
-#pragma unroll 1
-    for (int bt = 0; bt < nbatches; ++bt) {
-        float p[kGroups][G];
-        u32x2_t mid[kGroups], lo[kGroups];
-        uint32_t fill[kGroups];
-        // decisions of the batch, then its MID / LO loads
+    auto row0 = [&](int bt) { return t_first + bt * batch_stride; };
+    // a batch past the wave's last one is issued out of range: nothing is fetched
+    auto Lhi = [&](Batch& X, int bt) {
+        const uint32_t base = bt < nbatches ? uint32_t(row0(bt)) * kD : kSkip;
 #pragma unroll
-        for (int gr = 0; gr < kGroups; ++gr) {
-            const int t = t_first + bt * batch_stride + gr * 8 + r;
-            const bool valid = t < len;
+        for (int gr = 0; gr < KG; ++gr) X.hi[gr] = buf_load_b128(rs_hi, voff_hi + base + gr * 8 * kD);
+    };
+    auto Llg = [&](Batch& X, int bt) {
+        const uint32_t base = bt < nbatches ? uint32_t(row0(bt)) * 4u : kSkip;
+#pragma unroll
+        for (int g = 0; g < G; ++g) X.lg[g] = bits_float(buf_load_b32(rs_lg[g], voff_lg + base));
+    };
+    auto D = [&](Batch& X, int bt) {
+        uint32_t offm[KG], offl[KG];
+#pragma unroll
+        for (int gr = 0; gr < KG; ++gr) offm[gr] = offl[gr] = kSkip;
+        if (bt < nbatches) {   // uniform; arithmetic only -- the loads below are issued in any case
+            const int t0 = row0(bt);
+            const int nvalid = min(len - t0, RB);       // rows of the batch inside the sequence (may be <= 0)
+            float pj[G];
             int ahat = kAMin;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float x = score_x(lc[gr][g], Mg[g], a.c);
+                const float x = score_x(X.lg[g], Mg[g], a.c);
                 const int ag = score_a(x);
                 ahat = ag > ahat ? ag : ahat;
-                p[gr][g] = valid ? __builtin_amdgcn_exp2f(x) : 0.0f;
+                pj[g] = lane < nvalid ? __builtin_amdgcn_exp2f(x) : 0.0f;
+                z[g] += pj[g];
             }
-            const uint32_t ssplat = (uint32_t)(ahat + 64) * 0x01010101u;
-            const uint32_t hw[4] = {hc[gr].x, hc[gr].y, hc[gr].z, hc[gr].w};
-            uint32_t any1 = 0, any2 = 0;
+            const uint32_t ssw = __builtin_amdgcn_perm(0u, uint32_t(ahat + 64), 0x00000000u);   // (Ahat + 64) in every byte
+            uint32_t Fw;   // bit 7: the row-independent test for level >= 1 holds, bit 15: the one for level 2
+            if (vr.force >= 0) Fw = vr.force == 2 ? 0x8080u : (vr.force == 1 ? 0x0080u : 0u);
+            else Fw = (ahat + 1 + vr.wmax >= 3 ? 0x0080u : 0u) | (ahat + 1 + vr.wmax >= 7 ? 0x8000u : 0u);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t evp = (hw[i] >> 2) & 0x1F1F1F1Fu;
-                any1 |= evp + vr.B1[i] + ssplat;
-                any2 |= evp + vr.B2[i] + ssplat;
-            }
-            const uint64_t b1 = __ballot((any1 & 0x80808080u) != 0), b2 = __ballot((any2 & 0x80808080u) != 0);
-            const int sh = lane & 56;
-            const bool need1 = ((b1 >> sh) & 0xFFu) != 0 || (ahat + 1 + vr.wmax >= 3);
-            const bool need2 = ((b2 >> sh) & 0xFFu) != 0 || (ahat + 1 + vr.wmax >= 7);
-            int applied = need2 ? 2 : (need1 ? 1 : 0);
-            if (a.force_level >= 0) applied = a.force_level;
-            const uint32_t off = uint32_t(t) * (kD / 2) + cl * 8;
-            mid[gr] = buf_load_b64(rs_mid, (valid && applied >= 1) ? off : kSkip);
-            lo[gr] = buf_load_b64(rs_lo, (valid && applied >= 2) ? off : kSkip);
-            fill[gr] = fill_for_level(applied);
+            for (int gr = 0; gr < KG; ++gr) {
+                const uint32_t ss = (uint32_t)__builtin_amdgcn_ds_bpermute(src[gr], (int)ssw);
+                const uint32_t Fg = (uint32_t)__builtin_amdgcn_ds_bpermute(src[gr], (int)Fw);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    X.p[gr][g] = bits_float((uint32_t)__builtin_amdgcn_ds_bpermute(src[gr], (int)float_bits(pj[g])));
+                const uint32_t hw[4] = {X.hi[gr].x, X.hi[gr].y, X.hi[gr].z, X.hi[gr].w};
+                uint32_t any1 = Fg, any2 = Fg >> 8;   // bit 15 of Fg implies bit 7: stray bits in any1 do no harm
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t evp = (hw[i] >> 2) & 0x1F1F1F1Fu;
+                    const uint32_t S = evp + vr.B[i] + ss;
+                    any1 |= S;
+                    any2 |= S - 0x04040404u;
+                }
+                // bit 7 of a byte: level >= 1 needed; bit 6: level 2 needed (which implies the former)
+                const uint32_t flags = or_over_row((any1 & 0x80808080u) | ((any2 >> 1) & 0x40404040u));
+                const bool need1 = flags != 0, need2 = (flags & 0x40404040u) != 0;
+                const uint32_t off = voff_nib + uint32_t(t0) * (kD / 2) + gr * 8 * (kD / 2);
+                offm[gr] = need1 ? off : kSkip;
+                offl[gr] = need2 ? off : kSkip;
+                X.fill[gr] = need2 ? 0u : (need1 ? 0x08080808u : 0x80808080u);
 
-            if (DEBUG && valid) {
-                if (a.dbg.appliedV && cl == 0) a.dbg.appliedV[bh * Ncap + t] = (uint8_t)applied;
-                if (a.dbg.needV) {
-                    uint32_t nv[4];
+                if (DEBUG) {
+                    const int t = t0 + gr * 8 + r;
+                    if (t < len) {
+                        const int applied = need2 ? 2 : (need1 ? 1 : 0);
+                        if (a.dbg.appliedV && cl == 0) a.dbg.appliedV[bh * Ncap + t] = (uint8_t)applied;
+                        if (a.dbg.needV) {
+                            const int ah = int(ss & 0xFFu) - 64;
+                            uint32_t nv[4];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        nv[i] = 0;
+                            for (int i = 0; i < 4; ++i) {
+                                nv[i] = 0;
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            int ev = (int)((hw[i] >> (8 * k + 2)) & 31u);
-                            ev = ev < 1 ? 1 : ev;
-                            int need = level_for_mantissa_bits(10 + a.guard_bits - (vr.ehat[i * 4 + k] - (ahat + ev - 15)));
-                            if (a.force_level >= 0) need = a.force_level;
-                            nv[i] |= (uint32_t)need << (8 * k);
+                                for (int k = 0; k < 4; ++k) {
+                                    int ev = (int)((hw[i] >> (8 * k + 2)) & 31u);
+                                    ev = ev < 1 ? 1 : ev;
+                                    int need = level_for_mantissa_bits(10 + a.guard_bits - (vr.ehat[i * 4 + k] - (ah + ev - 15)));
+                                    if (a.force_level >= 0) need = a.force_level;
+                                    nv[i] |= (uint32_t)need << (8 * k);
+                                }
+                            }
+                            *reinterpret_cast<uint4*>(a.dbg.needV + (bh * Ncap + t) * kD + cl * 16) =
+                                make_uint4(nv[0], nv[1], nv[2], nv[3]);
                         }
                     }
-                    *reinterpret_cast<uint4*>(a.dbg.needV + (bh * Ncap + t) * kD + cl * 16) =
-                        make_uint4(nv[0], nv[1], nv[2], nv[3]);
                 }
             }
         }
-        // HI bytes and logits of the next batch go in flight behind the MID / LO loads
-        load_batch(bt + 1, hn, ln);
-        // multiply-adds of the batch
 #pragma unroll
-        for (int gr = 0; gr < kGroups; ++gr) {
+        for (int gr = 0; gr < KG; ++gr) {
+            X.mid[gr] = buf_load_b64(rs_mid, offm[gr]);
+            X.lo[gr] = buf_load_b64(rs_lo, offl[gr]);
+        }
+    };
+    auto F = [&](const Batch& X, int bt) {
+        if (bt >= nbatches) return;
+#pragma unroll
+        for (int gr = 0; gr < KG; ++gr) {
             uint32_t pa[4], pb[4];
-            assemble8_fill(hc[gr].x, hc[gr].y, mid[gr].x, lo[gr].x, fill[gr], pa);   // channels 0..7 of the slice
-            assemble8_fill(hc[gr].z, hc[gr].w, mid[gr].y, lo[gr].y, fill[gr], pb);   // channels 8..15
+            assemble8_fill(X.hi[gr].x, X.hi[gr].y, X.mid[gr].x, X.lo[gr].x, X.fill[gr], pa);   // channels 0..7 of the slice
+            assemble8_fill(X.hi[gr].z, X.hi[gr].w, X.mid[gr].y, X.lo[gr].y, X.fill[gr], pb);   // channels 8..15
             const float v[16] = {lo_half(pa[0]), lo_half(pa[1]), hi_half(pa[0]), hi_half(pa[1]),
                                  lo_half(pa[2]), lo_half(pa[3]), hi_half(pa[2]), hi_half(pa[3]),
                                  lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
                                  lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                z[g] += p[gr][g];
+            for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(p[gr][g], v[i], acc[g][i]);
-            }
+                for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(X.p[gr][g], v[i], acc[g][i]);
         }
+    };
+
+    Batch X, Y, Z;
+    if (PRE) {
 #pragma unroll
-        for (int gr = 0; gr < kGroups; ++gr) {
-            hc[gr] = hn[gr];
-#pragma unroll
-            for (int g = 0; g < G; ++g) lc[gr][g] = ln[gr][g];
-        }
+        for (int gr = 0; gr < KG; ++gr) X.hi[gr] = pre[gr];
+        if (!pre_ok) Lhi(X, 0);
+    } else {
+        Lhi(X, 0);
+    }
+    Llg(X, 0);
+    Lhi(Y, 1);
+    Llg(Y, 1);
+    D(X, 0);
+    // the three buffers rotate by name; rounds past the last batch issue nothing and compute nothing
+#pragma unroll 1
+    for (int i = 0; i < nbatches; i += 3) {
+        Lhi(Z, i + 2); Llg(Z, i + 2); D(Y, i + 1); F(X, i);
+        Lhi(X, i + 3); Llg(X, i + 3); D(Z, i + 2); F(Y, i + 1);
+        Lhi(Y, i + 4); Llg(Y, i + 4); D(X, i + 3); F(Z, i + 2);
     }
 }
 
-// sum acc / z over the 8 row lanes of a wave (lanes with the same lane % 8); afterwards lanes 0..7 hold the
-// wave's totals for their channel slices
+// sum acc over the 8 row lanes of a wave (lanes with the same lane % 8) and z over all lanes; afterwards
+// lanes 0..7 hold the wave's totals for their channel slices and every lane holds the wave's z
 template <int G>
 __device__ __forceinline__ void v_reduce_rows(float (&acc)[G][16], float (&z)[G])
 {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int g = 0; g < G; ++g) {
+        for (int o = 1; o < 64; o <<= 1) z[g] += __shfl_xor(z[g], o);
         for (int o = 8; o < 64; o <<= 1) {
-            z[g] += __shfl_xor(z[g], o);
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[g][i] += __shfl_xor(acc[g][i], o);
         }
+    }
 }
 
 // write out[b][h*G + g][:] = o / zsum for channel d (or zero for an empty sequence)

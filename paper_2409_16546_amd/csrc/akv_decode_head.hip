@@ -25,6 +25,7 @@ __device__ __forceinline__ void finish_append(const DecodeArgs& a, int b, int le
 }
 
 // groups of 8 rows per batch of the V side: what the register budget of the launch shape allows
+constexpr int kHeadVPre = 2;   // batches of V rows whose HI bytes a wave fetches while it waits for the mid step
 template <int G, int NT> constexpr int head_v_groups() { return NT <= 512 && G <= 2 ? 4 : 2; }
 
 template <int G, int NT, bool DEBUG>
@@ -47,6 +48,8 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     // q and K_colmax of the head are asked for first: everything below queues up behind them
     KLevelsIn<G> lin;
     k_levels_load<G>(a, b, h, lin);
+    int k_new_raw = 0;   // fused append: channel tid of the new token's K row (its use waits for the length)
+    if (a.k_new && tid < kD) k_new_raw = a.k_new[bh * kD + tid];
     if (tid == 0) len_s = min(a.lens[b], Ncap);
     __syncthreads();
     const int len_old = __builtin_amdgcn_readfirstlane(len_s);   // the same in every lane: keep it in a scalar register
@@ -58,7 +61,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     int k_new_bits = -1;
     uint32_t old_m = 0, old_l = 0;   // the nibble bytes the new token shares with its neighbour
     if (appended && tid < kD) {
-        k_new_bits = a.k_new[bh * kD + tid];
+        k_new_bits = k_new_raw;
         const size_t nib = k_nibble_index(bh, Ncap, len_old, tid);
         old_m = a.k_mid[nib];   // in flight together with the loads of the level computation
         old_l = a.k_lo[nib];
@@ -84,10 +87,6 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     const bool pre_any = blk < blk_end;
     if (pre_any) k_tile_pre(a, b, h, blk, kpre);
     const uint32_t colmax_used = k_levels_finish<G>(a, b, h, ks, true, k_new_bits, lin);
-    if (appended && tid >= NT - 64 && tid < NT - 64 + G) {   // a lane of the last wave per query head
-        const int g = tid - (NT - 64);
-        ks.new_logit[g] = new_token_logit<G>(ks, g);
-    }
     float wm[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) wm[g] = -INFINITY;
@@ -118,6 +117,9 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     if (lane == 0)
 #pragma unroll
         for (int g = 0; g < G; ++g) wmax_s[g][wave] = wm[g];
+    // The new token's logit: one lane per query head walks its fp16 row in channel order.  Wave 0 does it after
+    // its own tile -- the wave that is done first and would otherwise wait at the barrier below.
+    if (appended && tid < G) ks.new_logit[tid] = new_token_logit<G>(ks, tid);
     if (tid == 0 && a.k_new) {
         stores_done();   // ordered after the read of the length
         ticket = take_ticket(&a.flags[AKV_NFLAGS + b]);
@@ -126,9 +128,9 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     // of its first batch of V rows now (they depend on nothing).  Not when the row that is being appended lies
     // in that range -- its bytes are stored below.
     constexpr int KG = head_v_groups<G, NT>(), RB = 8 * KG;
-    const bool pre_ok = !(appended && len_old < RB * kWaves);
-    u32x4_t pre[KG];
-    v_prefetch_hi<KG>(a, b, h, wave * RB, pre_ok ? len : 0, pre);
+    const bool pre_ok = !(appended && len_old < kHeadVPre * RB * kWaves);
+    u32x4_t pre[kHeadVPre][KG];
+    v_prefetch_hi<KG, kHeadVPre>(a, b, h, wave * RB, RB * kWaves, pre_ok ? len : 0, pre);
     if (appended && tid < kD) {   // the new token goes into the planes (the block's lines were just read: they are in L2), K_colmax follows
         store_token_rmw(const_cast<uint8_t*>(a.k_hi), const_cast<uint8_t*>(a.k_mid), const_cast<uint8_t*>(a.k_lo),
                         const_cast<uint8_t*>(a.v_hi), const_cast<uint8_t*>(a.v_mid), const_cast<uint8_t*>(a.v_lo), bh,
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     }
     const int nbatch = (len + RB - 1) / RB;
     const int mine = nbatch > wave ? (nbatch - wave + kWaves - 1) / kWaves : 0;
-    v_rows<G, KG, DEBUG, true>(a, b, h, wave * RB, RB * kWaves, mine, len, vr, Mg, acc, z, pre, pre_ok);
+    v_rows<G, KG, DEBUG, kHeadVPre>(a, b, h, wave * RB, RB * kWaves, mine, len, vr, Mg, acc, z, pre, pre_ok);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll

@@ -110,8 +110,8 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
     }
-    const u32x4_t none[4] = {};
-    v_rows<G, 4, DEBUG>(a, b, h, c0 + wave * 32, 32 * kVWaves, kVChunk / (32 * kVWaves), len, vr, Mg, acc, z, none, false);
+    const u32x4_t none[1][4] = {};
+    v_rows<G, 4, DEBUG, 0>(a, b, h, c0 + wave * 32, 32 * kVWaves, kVChunk / (32 * kVWaves), len, vr, Mg, acc, z, none, false);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll

@@ -60,17 +60,20 @@ __device__ __forceinline__ uint32_t or_over_row(uint32_t v)
     return v;
 }
 
-// HI bytes of the first batch of a wave, issued early by a caller that has idle time before the V side can
+// HI bytes of the first NPRE batches of a wave, issued early by a caller that has idle time before the V side can
 // start (they depend on nothing but the row range).  Rows at or past len are not fetched.
-template <int KG>
-__device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h, int t_first, int len, u32x4_t (&hi)[KG])
+template <int KG, int NPRE>
+__device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int len,
+                                              u32x4_t (&hi)[NPRE][KG])
 {
     const int lane = threadIdx.x & 63;
     const size_t bh = size_t(b) * a.s.Hkv + h;
     const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.v_hi + bh * a.s.Ncap * kD, uint32_t(len) * kD);
     const uint32_t voff = uint32_t(t_first) * kD + uint32_t(lane >> 3) * kD + uint32_t(lane & 7) * 16;
 #pragma unroll
-    for (int gr = 0; gr < KG; ++gr) hi[gr] = buf_load_b128(rs_hi, voff + gr * 8 * kD);
+    for (int n = 0; n < NPRE; ++n)
+#pragma unroll
+        for (int gr = 0; gr < KG; ++gr) hi[n][gr] = buf_load_b128(rs_hi, voff + uint32_t(n * batch_stride + gr * 8) * kD);
 }
 
 // One wave walks token rows of (b, h) in batches of 8*KG rows (KG groups of 8 rows; lane -> row lane/8 of the
@@ -85,11 +88,11 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 // The descriptors end at row len, so rows at or past len read as zero without any per-lane test; their weight
 // is forced to zero.  acc accumulates sum_t p_t * v~_td per lane (to be reduced over the 8 row lanes, then
 // over waves, by the caller); z accumulates sum_t p_t per lane (to be summed over all 64 lanes).
-// PRE: pre holds the HI bytes of batch 0 (v_prefetch_hi) if pre_ok.
-template <int G, int KG, bool DEBUG, bool PRE = false>
+// NPRE > 0: pre holds the HI bytes of batches 0 .. NPRE-1 (v_prefetch_hi) if pre_ok.
+template <int G, int KG, bool DEBUG, int NPRE>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
                                        int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
-                                       float (&z)[G], const u32x4_t (&pre)[KG], bool pre_ok)
+                                       float (&z)[G], const u32x4_t (&pre)[NPRE > 0 ? NPRE : 1][KG], bool pre_ok)
 {
     constexpr int RB = 8 * KG;
     // wave-uniform by contract: scalar registers, scalar loop control
@@ -232,15 +235,17 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
     };
 
     Batch X, Y, Z;
-    if (PRE) {
+    if (NPRE >= 1) {
 #pragma unroll
-        for (int gr = 0; gr < KG; ++gr) X.hi[gr] = pre[gr];
-        if (!pre_ok) Lhi(X, 0);
-    } else {
-        Lhi(X, 0);
+        for (int gr = 0; gr < KG; ++gr) X.hi[gr] = pre[0][gr];
     }
+    if (NPRE >= 2) {
+#pragma unroll
+        for (int gr = 0; gr < KG; ++gr) Y.hi[gr] = pre[NPRE >= 2 ? 1 : 0][gr];
+    }
+    if (NPRE < 1 || !pre_ok) Lhi(X, 0);
     Llg(X, 0);
-    Lhi(Y, 1);
+    if (NPRE < 2 || !pre_ok) Lhi(Y, 1);
     Llg(Y, 1);
     D(X, 0);
     // the three buffers rotate by name; rounds past the last batch issue nothing and compute nothing

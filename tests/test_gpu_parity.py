@@ -89,6 +89,10 @@ CASES = [
     ("cfg1-force1", 1, dict(B=1, Hq=2, Hkv=2, N=600), None, dict(force_level=1)),
     ("cfg1-force2-control", 1, dict(B=1, Hq=2, Hkv=2, N=600), None, dict(force_level=2)),
     ("cfg2-scale", 2, dict(B=1, Hq=2, Hkv=2, N=520), None, dict(scale=0.05)),
+    # several blocks per wave and several chunks of the mid step on the head-per-workgroup kernel; 4096 is the
+    # longest sequence whose logits it keeps in registers
+    ("cfg2-mha-long", 2, dict(B=3, Hq=2, Hkv=2, N=5000), [5000, 4097, 4096], {}),
+    ("cfg4-gqa2-long", 4, dict(B=2, Hq=4, Hkv=2, N=4300), [4300, 2048], {}),
 ]
 
 
@@ -251,6 +255,37 @@ def test_fp16_yardstick_head_per_workgroup_variant(T, G):
 
 
 # ------------------------------------------------------------------------------------------ full bench size, sampled
+
+@pytest.mark.parametrize("G", [1, 2])
+def test_append_decode_in_one_call_across_block_chunk_and_prefetch_boundaries(T, G):
+    """The one-call decode step on the head-per-workgroup kernel while the lengths cross 256 (new K block), 512 (the
+    rows its waves fetch ahead), 1024, 2048 and 4096 (one chunk of the mid step for 512 / 1024 threads)."""
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    lens0 = [254, 510, 1022, 2046, 4094]
+    B, Hkv, Ncap = len(lens0), 2, 4352
+    Hq = Hkv * G
+    say(f"append + decode in one call across boundaries, G={G}, lens {lens0}")
+    w = workloads.make(2, B=B, Hq=Hq, Hkv=Hkv, N=4094)
+    oc = T.oracle_cache(w.k, w.v, lens0, Ncap)
+    gc = T.gpu_cache(w.k, w.v, lens0, Hq, Ncap)
+    gen = torch.Generator().manual_seed(11 + G)
+    for step in range(4):
+        kn = (torch.randn(B, Hkv, 1, 128, generator=gen) * 2).to(torch.float16)
+        vn = torch.randn(B, Hkv, 1, 128, generator=gen).to(torch.float16)
+        q = torch.randn(B, Hq, 128, generator=gen).to(torch.float16)
+        assert O.append(oc, T.bits(kn), T.bits(vn)) == 0
+        r = O.decode_attention(oc, T.bits(q))
+        dbg = A.DebugBuffers.allocate(gc)
+        out = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), q.to(DEV), dbg=dbg, path=1)
+        torch.cuda.synchronize()
+        T.assert_cache_equal(gc, oc)
+        T.assert_decode_equal(out, dbg, r, oc.lens.tolist(), G, f"G={G} step {step}")
+        # the same step without the exports (the kernel variant that is timed)
+        gc2_out = A.akv_decode_attention(gc, q.to(DEV), path=1)
+        torch.cuda.synchronize()
+        assert torch.equal(gc2_out, out)
+
 
 def test_cfg2_full_size_sampled_against_oracle(T):
     """BASELINE config 2 at full size in the launch configuration bench.py times (max_len = N, no debug

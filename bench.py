@@ -215,9 +215,18 @@ def main():
                                                           max_len=Ncap, path=2), steps)
         log(f"[bench] attention only (context {N}): AlignedKV {akv_only_us:.1f} us, control(16-bit) {ctl_us:.1f} us, "
             f"fp16 kernel {fp16_us:.1f} us, guard2 {g2_us:.1f} us, token-split path {split_us:.1f} us")
+        # the read ceiling of this device, by the library's plain streaming kernel over the same rotating footprint
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        stream_us = timed(lambda i: A.akv_stream_read(kp[i % R], sink), steps)
+        stream_gbps = kp[0].numel() * 2 / stream_us / 1e3
+        log(f"[bench] plain streaming read of {kp[0].numel() * 2 / 1e6:.0f} MB: {stream_us:.1f} us = {stream_gbps:.0f} GB/s")
         o16 = A.akv_fp16_decode_attention(kp[0], vp[0], lens_n, qd, max_len=Ncap, workspace=ws16)
         torch.cuda.synchronize()
         dev16 = (out_dbg - o16).double()
+        result["streaming_read_ceiling"] = {
+            "GBps": round(stream_gbps, 1), "frac_of_peak": round(stream_gbps / HBM_PEAK_GBS, 4),
+            "step_frac_of_ceiling": round(akv_bytes / (ms_per_step * 1e-3) / 1e9 / stream_gbps, 4),
+            "how": "akv_stream_read (16-byte loads, grid-stride) over the K tensors of the rotating fp16 copies, timed like a step"}
         result["vs_fp16_kernel"] = {
             "fp16_kernel_us": round(fp16_us, 2), "fp16_kernel_GBps": round(fp16_bytes / fp16_us / 1e3, 1),
             "fp16_kernel_frac_of_peak": round(fp16_bytes / fp16_us / 1e3 / HBM_PEAK_GBS, 4),

@@ -202,6 +202,16 @@ akv_status akv_fp16_decode_attention(const akv_shape *shape, const uint16_t *k, 
                                      const uint16_t *q, void *out, float scale, int32_t out_dtype, int32_t max_len,
                                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement aid: read `bytes` bytes (16-byte aligned, a multiple of 16) of
+ * device memory at buf once with a plain streaming kernel and discard them.
+ * Timed by a caller, it gives the read ceiling of the device that the decode
+ * kernels' effective bandwidth is put beside ("memory access latency ... is
+ * the bottleneck", the paper's premise).  sink: device uint32, never read,
+ * practically never written.  Nothing is allocated; asynchronous on stream.
+ */
+akv_status akv_stream_read(const void *buf, size_t bytes, uint32_t *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

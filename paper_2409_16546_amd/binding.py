@@ -20,7 +20,7 @@ AKV_TB = 256
 AKV_NFLAGS = 4
 AKV_MAX_TOPK = 64
 EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
-           "akv_decode_attention", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention"]
+           "akv_decode_attention", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read"]
 
 
 class AkvError(RuntimeError):
@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
         L.akv_append_decode_attention.restype = C.c_int
         L.akv_append_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                   C.POINTER(akv_params), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.akv_stream_read.restype = C.c_int
+        L.akv_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.akv_unpack.restype = C.c_int
         L.akv_unpack.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p]
         L.akv_fp16_decode_attention.restype = C.c_int
@@ -177,6 +179,11 @@ def akv_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, n_new: to
         assert n_new.dtype == torch.int32 and tuple(n_new.shape) == (cache.B,)
     s = cache.struct()
     _check(lib().akv_append(C.byref(s), _ptr(k_new), _ptr(v_new), _ptr(n_new), n, _stream()))
+
+
+def akv_stream_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    """Read the bytes of `buf` once with the library's plain streaming kernel (a measurement aid)."""
+    _check(lib().akv_stream_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()))
 
 
 def akv_unpack(cache: Cache) -> tuple[torch.Tensor, torch.Tensor]:

@@ -109,6 +109,15 @@ akv_status akv_append(const akv_cache* cache, const uint16_t* k_new, const uint1
     return AKV_OK;
 }
 
+akv_status akv_stream_read(const void* buf, size_t bytes, uint32_t* sink, void* stream)
+{
+    if (!buf || !sink) return fail(AKV_EINVAL, "buf / sink is NULL");
+    if ((reinterpret_cast<uintptr_t>(buf) & 15) || (bytes & 15)) return fail(AKV_EINVAL, "buf and bytes must be multiples of 16");
+    if (hipError_t e = akv::launch_stream_read(buf, bytes, sink, static_cast<hipStream_t>(stream)))
+        return hip_fail(e, "stream read launch");
+    return AKV_OK;
+}
+
 akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, void* stream)
 {
     if (akv_status st = check_cache(cache)) return st;

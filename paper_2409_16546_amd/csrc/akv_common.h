@@ -129,6 +129,7 @@ __device__ __forceinline__ uint32_t store_token(uint8_t* k_hi, uint8_t* k_mid, u
 hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
                          hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t* sink, hipStream_t st);
 hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, hipStream_t st);
 hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event);   // K kernel, V kernel
 hipError_t launch_decode_head(const DecodeArgs& a, hipStream_t st);                         // one kernel, a head per workgroup

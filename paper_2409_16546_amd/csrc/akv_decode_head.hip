@@ -43,16 +43,14 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     const int r = lane >> 3, cl = lane & 7;
     const int Hq = a.s.Hq, Hkv = a.s.Hkv, Ncap = a.s.Ncap;
     const size_t bh = size_t(b) * Hkv + h;
-    __shared__ int len_s;
     int ticket = -1;
     // q and K_colmax of the head are asked for first: everything below queues up behind them
     KLevelsIn<G> lin;
     k_levels_load<G>(a, b, h, lin);
     int k_new_raw = 0;   // fused append: channel tid of the new token's K row (its use waits for the length)
     if (a.k_new && tid < kD) k_new_raw = a.k_new[bh * kD + tid];
-    if (tid == 0) len_s = min(a.lens[b], Ncap);
-    __syncthreads();
-    const int len_old = __builtin_amdgcn_readfirstlane(len_s);   // the same in every lane: keep it in a scalar register
+    // the same address in every lane: a scalar load, the length lives in a scalar register
+    const int len_old = __builtin_amdgcn_readfirstlane(min(a.lens[b], Ncap));
     const bool appended = a.k_new && len_old + 1 <= Ncap;   // a full sequence keeps its tokens (counted at the end)
     // Fused append of one token: this workgroup owns every byte of (b, h).  The K side below runs over the
     // len_old tokens already stored and takes the new token's logit from its fp16 row directly, so nothing

@@ -164,10 +164,20 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     a.c = (float)(scale * 1.4426950408889634);
     a.topk = p.topk; a.guard_bits = p.guard_bits; a.force_level = p.force_level; a.out_dtype = p.out_dtype;
     a.max_len = p.max_len > 0 ? p.max_len : a.s.Ncap;
+    {   // V kernel of the token-split path: the largest chunk (fixed costs per workgroup: Rule 2 constants, pipeline
+        // start, partial results) that still leaves about four workgroups per compute unit
+        int chunk = akv::kVChunk;
+        const long pairs = long(a.s.B) * a.s.Hkv;
+        while (chunk < 4096 && pairs * ((a.max_len + 2 * chunk - 1) / (2 * chunk)) >= 1024) chunk *= 2;
+        a.vchunk = chunk;
+    }
     char* ws = static_cast<char*>(workspace);
     a.logits = reinterpret_cast<float*>(ws + w.logits);
     a.tilemax = reinterpret_cast<float*>(ws + w.tilemax);
     a.M = reinterpret_cast<float*>(ws + w.M);
+    a.hist = reinterpret_cast<int32_t*>(ws + w.hist);
+    a.cand_sel = reinterpret_cast<int32_t*>(ws + w.cand_sel);
+    a.cand_phat = reinterpret_cast<float*>(ws + w.cand_phat);
     a.Ehat = reinterpret_cast<int32_t*>(ws + w.Ehat);
     a.partO = reinterpret_cast<float*>(ws + w.partO);
     a.partZ = reinterpret_cast<float*>(ws + w.partZ);

@@ -18,6 +18,8 @@ constexpr int kMaxG = 8;           // query heads per KV head supported
 
 // K pass: one wave covers one 256-token block (4 consecutive tokens per lane).
 constexpr int kKWaves = 4;                         // waves per workgroup
+constexpr int kMidSlice = kTB * kKWaves;           // tokens per workgroup of the K kernel and of the mid kernel
+constexpr int kHistStride = 66;                    // ints per slice histogram in the workspace (65 buckets)
 // V pass: one workgroup covers kVChunk tokens; a wave reads 8 token rows per step.
 constexpr int kVWaves = 4;
 constexpr int kVChunk = 512;
@@ -27,6 +29,9 @@ struct WsLayout {
     size_t logits;   // float [B][Hq][Ncap]
     size_t tilemax;  // float [B][Hq][Ncap / 256]: per-wave-tile maxima of the K pass
     size_t M;        // float [B][Hq]
+    size_t hist;     // int32 [B][Hq][ceil(Ncap / 1024)][66]: per-slice histograms of score exponents (token-split path)
+    size_t cand_sel; // int32 [B][Hq][ceil(Ncap / 1024)][64]: per-slice top-k candidates, token | bucket << 24 (token-split path)
+    size_t cand_phat;// float, same shape: their weights
     size_t Ehat;     // int32 [B][Hkv][D]
     size_t partO;    // float [B][Hq][v_splits(Ncap)][D]
     size_t partZ;    // float [B][Hq][v_splits(Ncap)]
@@ -46,6 +51,9 @@ inline WsLayout ws_layout(const akv_shape& s)
     w.logits = off;  off = align256(off + bhq * s.Ncap * sizeof(float));
     w.tilemax = off; off = align256(off + bhq * (s.Ncap / kTB) * sizeof(float));
     w.M = off;       off = align256(off + bhq * sizeof(float));
+    w.hist = off;    off = align256(off + bhq * ((s.Ncap + kMidSlice - 1) / kMidSlice) * kHistStride * sizeof(int32_t));
+    w.cand_sel = off; off = align256(off + bhq * ((s.Ncap + kMidSlice - 1) / kMidSlice) * AKV_MAX_TOPK * sizeof(int32_t));
+    w.cand_phat = off; off = align256(off + bhq * ((s.Ncap + kMidSlice - 1) / kMidSlice) * AKV_MAX_TOPK * sizeof(float));
     w.Ehat = off;    off = align256(off + size_t(s.B) * s.Hkv * kD * sizeof(int32_t));
     w.partO = off;   off = align256(off + bhq * v_splits(s.Ncap) * kD * sizeof(float));
     w.partZ = off;   off = align256(off + bhq * v_splits(s.Ncap) * sizeof(float));
@@ -74,6 +82,10 @@ struct DecodeArgs {
     int32_t* Ehat;
     float* partO;
     float* partZ;
+    int vchunk;          // tokens per workgroup of the V kernel of the token-split path (multiple of kVChunk)
+    int32_t* hist;       // per-slice histograms of the token-split path
+    int32_t* cand_sel;   // per-slice candidates of the token-split path
+    float* cand_phat;
     int32_t* kcount;     // [B][Hkv] arrival counters (zero on entry, zero on exit)
     int32_t* vcount;
     akv_debug dbg;       // device pointers or NULL
@@ -214,6 +226,10 @@ __device__ __forceinline__ float load_agent(const float* p)
 __device__ __forceinline__ void store_agent(int32_t* p, int32_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t load_agent(const int32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // all of this wave's earlier stores have been acknowledged (and the compiler keeps them above this point)
 __device__ __forceinline__ void stores_done()

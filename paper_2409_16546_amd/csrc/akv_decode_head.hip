@@ -156,7 +156,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
             for (int i = 0; i < 4; ++i)
                 if ((len_old & 3) == i) own[g][i] = ks.new_logit[g];
     }
-    mid_step<G, NT, false>(a, b, h, len, ms, own, own_ok);
+    mid_step<G, NT>(a, b, h, len, ms, own, own_ok);
 
     // ---- V side: batches of 8*KG rows round-robin over the waves ----------------------------------------
     VRule vr;

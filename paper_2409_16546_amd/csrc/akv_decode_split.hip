@@ -1,8 +1,10 @@
 // Decode attention, token-split path: the tokens of every (sequence, KV head) are spread over many
-// workgroups (long contexts, few heads).  Two kernels:
-//   K kernel  Rule 1 levels + q.K~, one 256-token block per wave; the workgroup of a (sequence, KV head) that
-//             finishes last runs the mid step (max, score exponents, top-k, O_est, result exponents);
-//   V kernel  Rule 2 + S.V~ over 512-token chunks; the workgroup that finishes last combines the chunks.
+// workgroups (long contexts, few heads).  Three kernels:
+//   K kernel    Rule 1 levels + q.K~, one 256-token block per wave;
+//   mid kernel  max, score exponents and their histogram per 1024-token slice; the workgroup of a (sequence,
+//               KV head) that finishes last finds the top-k from the histograms and computes O_est and the result
+//               exponents;
+//   V kernel    Rule 2 + S.V~ over 512-token chunks; the workgroup that finishes last combines the chunks.
 // Sections "Quantization of K-Cache", "Quantization of V-Cache", "Runtime of AlignedKV".
 #include "akv_common.h"
 #include "akv_k_tile.h"
@@ -11,71 +13,238 @@
 
 namespace akv {
 
+// K kernel: workgroup = kKWaves waves = one slice of kMidSlice tokens of one (sequence, KV head); a wave walks one
+// 256-token block and leaves its logits and its block maximum in the workspace.
 template <int G>
 __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
 {
-    constexpr int kTile = kTB;   // tokens per wave
     __shared__ __align__(16) uint8_t kstage[kKWaves][kKStage];
     __shared__ KShared<G> ks;
-    __shared__ MidShared ms;
-    __shared__ float red_s[G][kKWaves];
-    __shared__ int last_s;
 
     const int h = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
+    const int lane = threadIdx.x & 63;
+    const int Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
     const int len = min(a.lens[b], Ncap);
-    const size_t bh = size_t(b) * Hkv + h;
-    const int tile = blockIdx.x * kKWaves + __builtin_amdgcn_readfirstlane(wave);
-    if (blockIdx.x * (kTile * kKWaves) >= len) return;   // whole workgroup beyond the sequence (uniform)
+    const int wave_u = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int blk = blockIdx.x * kKWaves + wave_u;
+    if (blockIdx.x * kMidSlice >= len) return;   // whole workgroup beyond the sequence (uniform)
 
     k_levels<G>(a, b, h, ks, blockIdx.x == 0);
-    if (tile * kTile < len) {                            // else this wave's tile is beyond the sequence
+    if (blk * kTB < len) {                       // else this wave's block is beyond the sequence
         float tm[G];
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
         const u32x4_t none[4] = {zero4, zero4, zero4, zero4};
         float lg[G][4];
-        k_tile<G>(a, b, h, tile, len, ks, kAuxSc1, tm, none, false, lg, &kstage[__builtin_amdgcn_readfirstlane(wave)][0]);
+        k_tile<G>(a, b, h, blk, len, ks, 0, tm, none, false, lg, &kstage[wave_u][0]);
         if (lane == 0)
 #pragma unroll
-            for (int g = 0; g < G; ++g)   // NB slots per head: one per block
-                store_agent(&a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + tile], tm[g]);
+            for (int g = 0; g < G; ++g) a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + blk] = tm[g];
     }
+}
 
-    // ---- the workgroup that finishes last for this (sequence, KV head) runs the mid step ------------
-    // Every workgroup waits until its device-scope stores are acknowledged and takes a ticket; the one that
-    // draws the last ticket reads all logits at device scope.  Nobody waits for anybody.
-    stores_done();
-    __syncthreads();
-    if (tid == 0) {
-        const int nwg = (len + kTile * kKWaves - 1) / (kTile * kKWaves);
-        last_s = take_ticket(&a.kcount[bh]) == nwg - 1;
-    }
-    __syncthreads();
-    if (!last_s) return;
-    // M = max over the tile maxima (exact, order-free)
-    const int ntiles = (len + kTile - 1) / kTile;
+// Mid kernel: workgroup = 256 threads = one slice of kMidSlice tokens of one (sequence, KV head).
+// Every workgroup derives the global max logit from the block maxima and, per query head, (1) builds the histogram
+// of score exponents of its slice and leaves it in the workspace as running sums over the buckets, (2) selects the
+// approximate top-k' of its own slice -- a superset of what the whole sequence can select from it, because the
+// cut bucket of the sequence is never later than the slice's own -- and leaves those candidates (token, bucket,
+// weight, in token order) in the workspace.  Device-scope stores; the producer waits for their acknowledgement
+// and takes a ticket.  The workgroup that draws the last ticket of the pair gives each query head of the group
+// to one of its waves: the wave adds the slices' running sums (the first bucket where the total reaches k' is the
+// cut), reads two words per slice to learn how many selected tokens precede each slice and which slices hold
+// any, and takes the selection out of those slices' candidate lists (lane = candidate, ballots give the order);
+// then all threads compute O_est and the result exponents head by head.  Everything that grows with the length
+// of the sequence is spread over the slices; every dependent step of the last workgroup is one round trip to
+// memory; nobody waits for anybody.
+template <int G>
+__global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
+{
+    constexpr int NT = 256, kWaves = NT / 64;
+    static_assert(kMidSlice == NT * 4, "a thread owns four tokens of the slice");
+    static_assert(kWaves <= kMidSets, "a selection per wave");
+    __shared__ MidShared ms;
+    __shared__ float red_s[G][kWaves];
+    __shared__ int last_s;
+    __shared__ int list_s[kWaves][AKV_MAX_TOPK], list_lt[kWaves][AKV_MAX_TOPK], list_eq[kWaves][AKV_MAX_TOPK];
+
+    const int slice = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
+    const int S = (Ncap + kMidSlice - 1) / kMidSlice;   // slices per query head in the workspace
+    const int len = min(a.lens[b], Ncap);
+    const size_t bh = size_t(b) * Hkv + h;
+    if (slice * kMidSlice >= len) return;   // uniform; also every empty sequence
+    const int nblk = (len + kTB - 1) / kTB, nsl = (len + kMidSlice - 1) / kMidSlice;
+    const int kk = a.topk < len ? a.topk : len;
+
+    for (int idx = tid; idx < kWaves * (kBuckets + 1); idx += NT) (&ms.cntw[0][0])[idx] = 0;
+    // M = max over the block maxima (exact, order-free)
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         float m = -INFINITY;
-        for (int i = tid; i < ntiles; i += 64 * kKWaves)
-            m = fmaxf(m, load_agent(&a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + i]));
+        for (int i = tid; i < nblk; i += NT) m = fmaxf(m, a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + i]);
         m = wave_max(m);
         if (lane == 0) red_s[g][wave] = m;
     }
     __syncthreads();
     if (tid < G) {
         float m = red_s[tid][0];
-        for (int w = 1; w < kKWaves; ++w) m = fmaxf(m, red_s[tid][w]);
+        for (int w = 1; w < kWaves; ++w) m = fmaxf(m, red_s[tid][w]);
         ms.M[tid] = m;
     }
     __syncthreads();
-    const float none4[G][4] = {};
-    mid_step<G, 64 * kKWaves, true>(a, b, h, len, ms, none4, false);
+
+    // ---- the slice: histogram and candidates of every query head ---------------------------------------------
+    {
+        const int t0 = slice * kMidSlice + tid * 4;
+        const int in_slice = min(len - slice * kMidSlice, kMidSlice);
+        const int kloc = kk < in_slice ? kk : in_slice;   // candidates per query head
+        float x[G][4];
+        int j[G][4];   // bucket j = -a_t (1000 at or past len)
+#pragma unroll
+        for (int g = 0; g < G; ++g) {   // the loads of all heads go out together
+            const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
+            const __amdgpu_buffer_rsrc_t rs_lg = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
+            const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rs_lg, uint32_t(t0) * 4u, 0, 0);   // past Ncap: zeros
+            const float lv[4] = {bits_float(w.x), bits_float(w.y), bits_float(w.z), bits_float(w.w)};
+            const float M = ms.M[g];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[g][i] = score_x(lv[i], M, a.c);
+                j[g][i] = t0 + i < len ? -score_a(x[g][i]) : 1000;
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
+            if (a.dbg.a) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (j[g][i] <= 64) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[g][i]);
+            }
+            mid_select_chunk<NT>(ms, 0, x[g], j[g], t0, kloc);   // per-wave histograms in ms.cntw, candidates in set 0
+            if (wave == 0) {   // running sums over the buckets of the slice's histogram
+                int incl = 0;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) incl += ms.cntw[w][lane];
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int u = __shfl_up(incl, o);
+                    if (lane >= o) incl += u;
+                }
+                int32_t* dst = a.hist + (hq * S + slice) * kHistStride;
+                store_agent(&dst[lane], incl);                      // tokens in buckets 0..lane
+                if (lane == 63) store_agent(&dst[64], in_slice);    // all tokens of the slice
+            }
+            __syncthreads();   // the candidates are in LDS; everybody is done with the histograms
+            if (tid < AKV_MAX_TOPK) {
+                const size_t at = (hq * S + slice) * AKV_MAX_TOPK + tid;
+                store_agent(&a.cand_sel[at], tid < kloc ? (ms.sel[0][tid] | (ms.selj[0][tid] << 24)) : -1);
+                store_agent(&a.cand_phat[at], tid < kloc ? ms.phat[0][tid] : 0.0f);
+            }
+            for (int idx = tid; idx < kWaves * (kBuckets + 1); idx += NT) (&ms.cntw[0][0])[idx] = 0;
+            __syncthreads();
+        }
+    }
+    stores_done();
+    __syncthreads();
+    if (tid == 0) last_s = take_ticket(&a.kcount[bh]) == nsl - 1;
+    __syncthreads();
+    if (!last_s) return;
+
+    // ---- the workgroup that finished last for this (sequence, KV head) ------------------------------------
+    int ehat = 32767;   // min over the group of the result exponent of channel tid (tid < D)
+    for (int g0 = 0; g0 < G; g0 += kWaves) {
+        const int g = g0 + wave;
+        if (g < G) {   // wave-uniform: this wave collects the selection of query head g
+            const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
+            const int32_t* hist = a.hist + hq * S * kHistStride;
+            // running sums over the buckets, added over the slices: lane = bucket (0..63); 16 loads in flight
+            int tot = 0;
+            for (int s0 = 0; s0 < nsl; s0 += 16) {
+                int v[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = s0 + i < nsl ? load_agent(&hist[(s0 + i) * kHistStride + lane]) : 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) tot += v[i];
+            }
+            const uint64_t reached = __ballot(tot >= kk);
+            const int J = reached ? __builtin_ctzll(reached) : 64;   // bucket 64 is the cut only if none before it is
+            const int below = J == 0 ? 0 : __shfl(tot, J - 1);
+            const int fromcut = kk - below;
+            // slices that hold selected tokens, with the number of tokens of each kind before them: lane = slice
+            int nlist = 0, carry_lt = 0, carry_eq = 0;
+            for (int s0 = 0; s0 < nsl; s0 += 64) {
+                const int s = s0 + lane;
+                int c_lt = 0, c_le = 0;
+                if (s < nsl) {
+                    if (J > 0) c_lt = load_agent(&hist[s * kHistStride + J - 1]);
+                    c_le = load_agent(&hist[s * kHistStride + J]);
+                }
+                const int c_eq = c_le - c_lt;
+                int i_lt = c_lt, i_eq = c_eq;   // inclusive scan over the lanes
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int u_lt = __shfl_up(i_lt, o), u_eq = __shfl_up(i_eq, o);
+                    if (lane >= o) {
+                        i_lt += u_lt;
+                        i_eq += u_eq;
+                    }
+                }
+                const int p_lt = carry_lt + i_lt - c_lt, p_eq = carry_eq + i_eq - c_eq;   // exclusive prefixes
+                const bool holds = c_lt > 0 || (c_eq > 0 && p_eq < fromcut);
+                const uint64_t hb = __ballot(holds);   // at most kk such slices in all: each holds a selected token
+                if (holds) {
+                    const int at = nlist + __builtin_amdgcn_mbcnt_hi((uint32_t)(hb >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hb, 0));
+                    list_s[wave][at] = s;
+                    list_lt[wave][at] = p_lt;
+                    list_eq[wave][at] = p_eq;
+                }
+                nlist += __builtin_popcountll(hb);
+                carry_lt += __shfl(i_lt, 63);
+                carry_eq += __shfl(i_eq, 63);
+            }
+            // ---- the selection out of those slices' candidates: lane = candidate (token order inside a slice) ------
+            constexpr int kAhead = 8;   // slices of the list whose candidates are in flight
+            int cs[kAhead];
+            float cp[kAhead];
+            auto fetch = [&](int e, int& sel, float& phat) {
+                const bool on = e < nlist;
+                const size_t at = (hq * S + (on ? list_s[wave][e] : 0)) * AKV_MAX_TOPK + lane;
+                sel = on ? load_agent(&a.cand_sel[at]) : -1;
+                phat = on ? load_agent(&a.cand_phat[at]) : 0.0f;
+            };
+#pragma unroll
+            for (int k = 0; k < kAhead; ++k) fetch(k, cs[k], cp[k]);
+            for (int e = 0; e < nlist; e += kAhead) {
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) {
+                    if (e + k < nlist) {   // uniform
+                        const int jj = cs[k] >> 24, t = cs[k] & 0xFFFFFF;
+                        const bool is_lt = cs[k] >= 0 && jj < J, is_eq = cs[k] >= 0 && jj == J;
+                        const uint64_t b_lt = __ballot(is_lt), b_eq = __ballot(is_eq);
+                        const int n_lt = list_lt[wave][e + k] + __builtin_amdgcn_mbcnt_hi((uint32_t)(b_lt >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b_lt, 0));
+                        const int n_eq = list_eq[wave][e + k] + __builtin_amdgcn_mbcnt_hi((uint32_t)(b_eq >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b_eq, 0));
+                        if (is_lt || (is_eq && n_eq < fromcut)) {
+                            const int pos = n_lt + (n_eq < fromcut ? n_eq : fromcut);
+                            ms.sel[wave][pos] = t;
+                            ms.phat[wave][pos] = cp[k];
+                        }
+                    }
+                    fetch(e + k + kAhead, cs[k], cp[k]);
+                }
+            }
+            if (lane == 0) a.M[hq] = ms.M[g];
+        }
+        __syncthreads();
+        for (int w = 0; w < kWaves && g0 + w < G; ++w)   // all threads, head by head (ends with a barrier)
+            mid_oest<NT>(a, bh, size_t(b) * Hq + size_t(h) * G + g0 + w, kk, ms, w, ehat);
+    }
+    if (tid < kD) {
+        a.Ehat[bh * kD + tid] = ehat;
+        if (a.dbg.Ehat) a.dbg.Ehat[bh * kD + tid] = (int16_t)ehat;
+    }
     if (tid == 0) store_agent(&a.kcount[bh], 0);   // ready for the next call
 }
 
-// Workgroup = kVWaves waves, one (sequence, KV head, 512-token chunk); wave w takes the batches of 32 rows
+// Workgroup = kVWaves waves, one (sequence, KV head, kVChunk-token chunk); wave w takes the batches of rows
 // w, w + kVWaves, ... of the chunk.
 template <int G, bool DEBUG>
 __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
@@ -88,7 +257,8 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     const int r = lane >> 3, cl = lane & 7;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const int len = min(a.lens[b], Ncap);
-    const int c0 = split * kVChunk;
+    const int vchunk = a.vchunk;   // tokens per workgroup: a multiple of kVChunk chosen at launch
+    const int c0 = split * vchunk;
     const size_t bh = size_t(b) * Hkv + h;
     const int nsplit = v_splits(Ncap);
     if (c0 >= len) {                                    // uniform: chunk beyond the sequence
@@ -110,8 +280,11 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
     }
-    const u32x4_t none[1][4] = {};
-    v_rows<G, 4, DEBUG, 0>(a, b, h, c0 + wave * 32, 32 * kVWaves, kVChunk / (32 * kVWaves), len, vr, Mg, acc, z, none, false);
+    // 16 rows per batch, HI bytes fetched four batches ahead: the accumulators of a group of query heads leave room
+    // for few waves per SIMD, so each wave keeps more bytes in flight
+    constexpr int KG = 2, RB = 8 * KG, DL = 4;
+    const u32x4_t none[1][KG] = {};
+    v_rows<G, KG, DEBUG, 0, DL>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll
@@ -134,7 +307,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 
     // ---- the workgroup that finishes last for this (sequence, KV head) combines the chunks -------------
     // out = sum_chunks O / sum_chunks Z: every chunk used the same global max, so nothing is rescaled.
-    const int used = v_splits(len);
+    const int used = (len + vchunk - 1) / vchunk;
     stores_done();
     __syncthreads();
     if (tid == 0) last_s = take_ticket(&a.vcount[bh]) == used - 1;
@@ -160,9 +333,11 @@ static hipError_t launch_split_g(const DecodeArgs& a, hipStream_t st, hipEvent_t
     const dim3 kgrid((a.max_len + tile - 1) / tile, a.s.Hkv, a.s.B), kblock(64 * kKWaves);
     hipLaunchKernelGGL((split_k_kernel<G>), kgrid, kblock, 0, st, a);
     if (hipError_t e = hipGetLastError()) return e;
+    hipLaunchKernelGGL((split_mid_kernel<G>), kgrid, dim3(256), 0, st, a);   // one workgroup per slice here as well
+    if (hipError_t e = hipGetLastError()) return e;
     if (mid_event)
         if (hipError_t e = hipEventRecord(mid_event, st)) return e;
-    const dim3 vgrid(v_splits(a.max_len), a.s.Hkv, a.s.B), vblock(64 * kVWaves);
+    const dim3 vgrid((a.max_len + a.vchunk - 1) / a.vchunk, a.s.Hkv, a.s.B), vblock(64 * kVWaves);
     if (a.dbg.needV || a.dbg.appliedV) hipLaunchKernelGGL((split_v_kernel<G, true>), vgrid, vblock, 0, st, a);
     else hipLaunchKernelGGL((split_v_kernel<G, false>), vgrid, vblock, 0, st, a);
     return hipGetLastError();

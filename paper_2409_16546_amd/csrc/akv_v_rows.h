@@ -78,18 +78,19 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 
 // One wave walks token rows of (b, h) in batches of 8*KG rows (KG groups of 8 rows; lane -> row lane/8 of the
 // group and the 16-channel slice lane%8): batch i covers rows t_first + i*batch_stride .. + 8*KG - 1,
-// i < nbatches.  Three stages per batch, software-pipelined over three named buffers:
+// i < nbatches.  Three stages per batch, software-pipelined over DL + 1 named buffers:
 //   L  issue the HI loads and the logit loads (lane j < 8*KG holds the logit of row j of the batch);
 //   D  softmax weight and score exponent once per row, handed to the 8 lanes of the row by lane permutes;
 //      Rule 2 on the HI bytes; MID / LO loads of the rows that need them (the others are issued out of
 //      range: nothing is fetched);
 //   F  assemble the fp16 values, multiply-adds.
-// Iteration i runs L(i+2), D(i+1), F(i): every load has a whole iteration of arithmetic to arrive.
+// Round i runs L(i+DL), D(i+1), F(i): every load has at least a whole round of arithmetic to arrive; a kernel
+// with few waves per SIMD raises DL to keep enough bytes in flight.
 // The descriptors end at row len, so rows at or past len read as zero without any per-lane test; their weight
 // is forced to zero.  acc accumulates sum_t p_t * v~_td per lane (to be reduced over the 8 row lanes, then
 // over waves, by the caller); z accumulates sum_t p_t per lane (to be summed over all 64 lanes).
 // NPRE > 0: pre holds the HI bytes of batches 0 .. NPRE-1 (v_prefetch_hi) if pre_ok.
-template <int G, int KG, bool DEBUG, int NPRE>
+template <int G, int KG, bool DEBUG, int NPRE, int DL = 2>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
                                        int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
                                        float (&z)[G], const u32x4_t (&pre)[NPRE > 0 ? NPRE : 1][KG], bool pre_ok)
@@ -234,26 +235,32 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
         }
     };
 
-    Batch X, Y, Z;
-    if (NPRE >= 1) {
+    // R = DL + 1 named buffers: round i runs L(i + DL), D(i + 1), F(i); the buffer L fills is the one F emptied in
+    // the round before.  The loop is unrolled R times so that every buffer index is a constant.
+    constexpr int R = DL + 1;
+    static_assert(DL >= 2 && NPRE <= DL, "the HI loads run at least two batches ahead");
+    Batch ring[R];
 #pragma unroll
-        for (int gr = 0; gr < KG; ++gr) X.hi[gr] = pre[0][gr];
-    }
-    if (NPRE >= 2) {
+    for (int k = 0; k < DL; ++k) {
+        if (k < NPRE) {
 #pragma unroll
-        for (int gr = 0; gr < KG; ++gr) Y.hi[gr] = pre[NPRE >= 2 ? 1 : 0][gr];
+            for (int gr = 0; gr < KG; ++gr) ring[k].hi[gr] = pre[k < NPRE ? k : 0][gr];
+            if (!pre_ok) Lhi(ring[k], k);
+        } else {
+            Lhi(ring[k], k);
+        }
+        Llg(ring[k], k);
     }
-    if (NPRE < 1 || !pre_ok) Lhi(X, 0);
-    Llg(X, 0);
-    if (NPRE < 2 || !pre_ok) Lhi(Y, 1);
-    Llg(Y, 1);
-    D(X, 0);
-    // the three buffers rotate by name; rounds past the last batch issue nothing and compute nothing
+    D(ring[0], 0);
 #pragma unroll 1
-    for (int i = 0; i < nbatches; i += 3) {
-        Lhi(Z, i + 2); Llg(Z, i + 2); D(Y, i + 1); F(X, i);
-        Lhi(X, i + 3); Llg(X, i + 3); D(Z, i + 2); F(Y, i + 1);
-        Lhi(Y, i + 4); Llg(Y, i + 4); D(X, i + 3); F(Z, i + 2);
+    for (int i = 0; i < nbatches; i += R) {   // rounds past the last batch issue nothing and compute nothing
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            Lhi(ring[(k + DL) % R], i + k + DL);
+            Llg(ring[(k + DL) % R], i + k + DL);
+            D(ring[(k + 1) % R], i + k + 1);
+            F(ring[k], i + k);
+        }
     }
 }
 

@@ -1,4 +1,5 @@
 // C ABI of the library (declared in include/akv.h): argument checks, workspace carving, launches.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -164,12 +165,22 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     a.c = (float)(scale * 1.4426950408889634);
     a.topk = p.topk; a.guard_bits = p.guard_bits; a.force_level = p.force_level; a.out_dtype = p.out_dtype;
     a.max_len = p.max_len > 0 ? p.max_len : a.s.Ncap;
-    {   // V kernel of the token-split path: the largest chunk (fixed costs per workgroup: Rule 2 constants, pipeline
-        // start, partial results) that still leaves about four workgroups per compute unit
-        int chunk = akv::kVChunk;
+    {   // V kernel of the token-split path: one round of workgroups that fills the device -- the tokens of a
+        // (sequence, KV head) pair are cut into as many chunks as there are resident workgroups per pair, so that
+        // the fixed costs per workgroup (Rule 2 constants, pipeline start, partial results) are paid once per slot
+        static int cus = 0;
+        if (cus == 0) {
+            int dev = 0, n = 0;
+            if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+            else cus = 256;
+        }
+        const int G = a.s.Hq / a.s.Hkv;
+        const int per_cu = G <= 1 ? 4 : (G <= 4 ? 3 : 1);   // resident V workgroups per compute unit (register budget)
         const long pairs = long(a.s.B) * a.s.Hkv;
-        while (chunk < 4096 && pairs * ((a.max_len + 2 * chunk - 1) / (2 * chunk)) >= 1024) chunk *= 2;
-        a.vchunk = chunk;
+        const long per_pair = std::max(1L, long(cus) * per_cu / pairs);
+        long chunk = (a.max_len + per_pair - 1) / per_pair;
+        chunk = (chunk + 63) / 64 * 64;                       // whole batches of rows for every wave
+        a.vchunk = int(std::max(long(akv::kVChunk), chunk));
     }
     char* ws = static_cast<char*>(workspace);
     a.logits = reinterpret_cast<float*>(ws + w.logits);

@@ -282,7 +282,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     }
     // 16 rows per batch, HI bytes fetched four batches ahead: the accumulators of a group of query heads leave room
     // for few waves per SIMD, so each wave keeps more bytes in flight
-    constexpr int KG = 2, RB = 8 * KG, DL = 4;
+    constexpr int KG = G >= 4 ? 1 : 2, RB = 8 * KG, DL = G == 2 ? 4 : 3;
     const u32x4_t none[1][KG] = {};
     v_rows<G, KG, DEBUG, 0, DL>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
     v_reduce_rows<G>(acc, z);
@@ -317,9 +317,19 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
         const int g = idx / kD, d = idx % kD;
         const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
         float o = 0.0f, zsum = 0.0f;
-        for (int sp = 0; sp < used; ++sp) {
-            o += load_agent(&a.partO[(hq * nsplit + sp) * kD + d]);
-            zsum += load_agent(&a.partZ[hq * nsplit + sp]);
+        for (int sp0 = 0; sp0 < used; sp0 += 8) {   // eight chunks' words in flight; the additions stay in chunk order
+            float po[8], pz[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bool on = sp0 + i < used;
+                po[i] = on ? load_agent(&a.partO[(hq * nsplit + sp0 + i) * kD + d]) : 0.0f;
+                pz[i] = on ? load_agent(&a.partZ[hq * nsplit + sp0 + i]) : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                o += po[i];
+                zsum += pz[i];
+            }
         }
         store_out(a, hq, d, o / zsum);
     }

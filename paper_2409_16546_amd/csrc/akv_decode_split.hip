@@ -76,7 +76,6 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
     const int nblk = (len + kTB - 1) / kTB, nsl = (len + kMidSlice - 1) / kMidSlice;
     const int kk = a.topk < len ? a.topk : len;
 
-    for (int idx = tid; idx < kWaves * (kBuckets + 1); idx += NT) (&ms.cntw[0][0])[idx] = 0;
     // M = max over the block maxima (exact, order-free)
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -93,39 +92,49 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
     }
     __syncthreads();
 
-    // ---- the slice: histogram and candidates of every query head ---------------------------------------------
+    // ---- the slice: histogram and candidates, a wave per query head (lane -> 16 consecutive tokens; everything
+    // below is wave-local: LDS serves a wave's accesses in order, no barrier) ------------------------------------
     {
-        const int t0 = slice * kMidSlice + tid * 4;
         const int in_slice = min(len - slice * kMidSlice, kMidSlice);
         const int kloc = kk < in_slice ? kk : in_slice;   // candidates per query head
-        float x[G][4];
-        int j[G][4];   // bucket j = -a_t (1000 at or past len)
-#pragma unroll
-        for (int g = 0; g < G; ++g) {   // the loads of all heads go out together
+        const int t0 = slice * kMidSlice + lane * 16;
+        for (int g = wave; g < G; g += kWaves) {
             const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
             const __amdgpu_buffer_rsrc_t rs_lg = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
-            const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rs_lg, uint32_t(t0) * 4u, 0, 0);   // past Ncap: zeros
-            const float lv[4] = {bits_float(w.x), bits_float(w.y), bits_float(w.z), bits_float(w.w)};
             const float M = ms.M[g];
+            u32x4_t w[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                x[g][i] = score_x(lv[i], M, a.c);
-                j[g][i] = t0 + i < len ? -score_a(x[g][i]) : 1000;
+            for (int q4 = 0; q4 < 4; ++q4) w[q4] = __builtin_amdgcn_raw_buffer_load_b128(rs_lg, uint32_t(t0 + 4 * q4) * 4u, 0, 0);   // past Ncap: zeros
+            int* hw = &ms.cntw[wave][0];
+            hw[lane] = 0;
+            if (lane < 2) hw[64 + lane] = 0;
+            float x[16];
+            int j[16];   // bucket j = -a_t (1000 at or past len)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const float lv[4] = {bits_float(w[q4].x), bits_float(w[q4].y), bits_float(w[q4].z), bits_float(w[q4].w)};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int ii = 4 * q4 + i;
+                    x[ii] = score_x(lv[i], M, a.c);
+                    j[ii] = t0 + ii < len ? -score_a(x[ii]) : 1000;
+                }
             }
-        }
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
-            if (a.dbg.a) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (j[g][i] <= 64) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[g][i]);
+            for (int i = 0; i < 16; ++i) {
+                if (j[i] <= 64) {
+                    atomicAdd(&hw[j[i]], 1);
+                    if (a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[i]);
+                }
             }
-            mid_select_chunk<NT>(ms, 0, x[g], j[g], t0, kloc);   // per-wave histograms in ms.cntw, candidates in set 0
-            if (wave == 0) {   // running sums over the buckets of the slice's histogram
-                int incl = 0;
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) incl += ms.cntw[w][lane];
+            __builtin_amdgcn_wave_barrier();
+            const int c = hw[lane];   // bucket `lane` of the slice's histogram
+            int J, below;
+            mid_find_cut(c, kloc, J, below);   // the slice's own cut: never earlier than the sequence's
+            const int fromcut = kloc - below;
+            {   // running sums over the buckets, for the workgroup that merges the slices
+                int incl = c;
                 for (int o = 1; o < 64; o <<= 1) {
                     const int u = __shfl_up(incl, o);
                     if (lane >= o) incl += u;
@@ -134,14 +143,35 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                 store_agent(&dst[lane], incl);                      // tokens in buckets 0..lane
                 if (lane == 63) store_agent(&dst[64], in_slice);    // all tokens of the slice
             }
-            __syncthreads();   // the candidates are in LDS; everybody is done with the histograms
-            if (tid < AKV_MAX_TOPK) {
-                const size_t at = (hq * S + slice) * AKV_MAX_TOPK + tid;
-                store_agent(&a.cand_sel[at], tid < kloc ? (ms.sel[0][tid] | (ms.selj[0][tid] << 24)) : -1);
-                store_agent(&a.cand_phat[at], tid < kloc ? ms.phat[0][tid] : 0.0f);
+            // the candidates in token order: tokens of each kind in lower lanes from five ballots per kind (one per
+            // bit of the lane's count, at most 16)
+            int c_lt = 0, c_eq = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                c_lt += j[i] < J;
+                c_eq += j[i] == J;
             }
-            for (int idx = tid; idx < kWaves * (kBuckets + 1); idx += NT) (&ms.cntw[0][0])[idx] = 0;
-            __syncthreads();
+            int n_lt = 0, n_eq = 0;
+#pragma unroll
+            for (int bit = 0; bit < 5; ++bit) {
+                const uint64_t b_lt = __ballot((c_lt >> bit) & 1), b_eq = __ballot((c_eq >> bit) & 1);
+                n_lt += __builtin_amdgcn_mbcnt_hi((uint32_t)(b_lt >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b_lt, 0)) << bit;
+                n_eq += __builtin_amdgcn_mbcnt_hi((uint32_t)(b_eq >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b_eq, 0)) << bit;
+            }
+            const size_t base = (hq * S + slice) * AKV_MAX_TOPK;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const bool is_lt = j[i] < J, is_eq = j[i] == J;
+                if (is_lt || (is_eq && n_eq < fromcut)) {
+                    const int pos = n_lt + (n_eq < fromcut ? n_eq : fromcut);
+                    const float fl = floorf(x[i]);
+                    store_agent(&a.cand_sel[base + pos], (t0 + i) | (j[i] << 24));
+                    store_agent(&a.cand_phat[base + pos], ldexpf(1.0f + (x[i] - fl), -j[i]));   // as mid_emit
+                }
+                n_lt += is_lt;
+                n_eq += is_eq;
+            }
+            if (lane >= kloc) store_agent(&a.cand_sel[base + lane], -1);   // no candidate
         }
     }
     stores_done();

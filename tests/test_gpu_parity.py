@@ -316,3 +316,49 @@ def test_cfg2_full_size_sampled_against_oracle(T):
                                (sub.lvlK, sub.logits, sub.a, sub.sel, sub.oest, sub.Ehat, sub.needV, sub.appliedV)])
         err, rl2 = T.assert_decode_equal(out_plain[b:b + 1, h:h + 1], sub, r, [N], 1, f"cfg2 b={b} h={h}")
         say(f"  b={b} h={h}: max-abs {err:.2e} rel-L2 {rl2:.2e}")
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_full_size_configs_3_to_5_sampled_against_oracle(T, cfg):
+    """BASELINE configs 3-5 at full size with the library's choice of path: config 3 (B16, MHA, 8192 tokens; the
+    last token is appended inside the step) runs the head-per-workgroup kernel with two blocks per wave and two
+    chunks in the mid step; configs 4 and 5 (GQA 32/8, 32768 tokens / ragged lengths up to 131072) run the
+    token-split kernels.  Three sampled (sequence, KV head) pairs are recomputed by the oracle."""
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    w = workloads.make(cfg)
+    G, N = w.Hq // w.Hkv, w.Ncap
+    lens = w.lens.tolist()
+    say(f"full size: cfg{cfg} B{w.B} H{w.Hq}/{w.Hkv} Ncap{N} lens {lens[:4]}...")
+    q = w.q.to(DEV)
+    dbg = None
+    if w.append_last:
+        before = [n - 1 for n in lens]
+        gc = T.gpu_cache(w.k, w.v, before, w.Hq, N)
+        kn = torch.stack([w.k[b, :, lens[b] - 1:lens[b]] for b in range(w.B)]).contiguous()
+        vn = torch.stack([w.v[b, :, lens[b] - 1:lens[b]] for b in range(w.B)]).contiguous()
+        dbg = A.DebugBuffers.allocate(gc)
+        out = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), q, max_len=max(lens), dbg=dbg)
+    else:
+        gc = T.gpu_cache(w.k, w.v, lens, w.Hq, N)
+        dbg = A.DebugBuffers.allocate(gc)
+        out = A.akv_decode_attention(gc, q, max_len=max(lens), dbg=dbg)
+    plain = A.akv_decode_attention(gc, q, max_len=max(lens))           # the launch without exports
+    torch.cuda.synchronize()
+    assert torch.equal(plain, out)
+    assert gc.lens.cpu().tolist() == lens
+    rng = np.random.default_rng(cfg)
+    for b, h in zip(rng.integers(0, w.B, 3), rng.integers(0, w.Hkv, 3)):
+        b, h = int(b), int(h)
+        n = lens[b]
+        hs = slice(h * G, (h + 1) * G)
+        oc = T.oracle_cache(w.k[b:b + 1, h:h + 1, :n], w.v[b:b + 1, h:h + 1, :n], [n], N)
+        r = O.decode_attention(oc, T.bits(w.q[b:b + 1, hs]))
+        for name in ("k_hi", "k_mid", "k_lo", "v_hi", "v_mid", "v_lo"):   # the planes of this pair, byte for byte
+            plane = getattr(gc, name).view(w.B, w.Hkv, -1)[b, h].cpu().numpy()
+            assert np.array_equal(plane, getattr(oc, name).reshape(-1)), f"cfg{cfg} b={b} h={h}: plane {name} differs"
+        sub = A.DebugBuffers(*[x.contiguous() for x in (
+            dbg.lvlK[b:b + 1, h:h + 1], dbg.logits[b:b + 1, hs], dbg.a[b:b + 1, hs], dbg.sel[b:b + 1, hs],
+            dbg.oest[b:b + 1, hs], dbg.Ehat[b:b + 1, h:h + 1], dbg.needV[b:b + 1, h:h + 1], dbg.appliedV[b:b + 1, h:h + 1])])
+        err, rl2 = T.assert_decode_equal(out[b:b + 1, hs], sub, r, [n], G, f"cfg{cfg} b={b} h={h}")
+        say(f"  b={b} h={h} len={n}: max-abs {err:.2e} rel-L2 {rl2:.2e}")

@@ -42,11 +42,143 @@ __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t
     }
 }
 
+// Bulk append (prefill): one workgroup of 256 threads per (sequence, KV head, 256-token K block touched).
+// V rows need no transposition: a thread turns 16 channels of a row (32 bytes in) into 16 + 8 + 8 bytes of the three
+// planes.  A K block that the new tokens cover completely goes through an LDS tile [256 tokens][128 channels] and
+// leaves as 16-byte pieces of the channel-major runs; a block they cover only partly (the first one after a
+// sequence that does not end on a block boundary, the last one) is stored token by token, thread d being the only
+// writer of column d.  K_colmax: a 16-bit maximum through compare-and-swap on the enclosing word.
+constexpr int kTilePad = kD + 2;   // halves per token row of the LDS tile: rows 65 words apart, columns conflict-free
+
+__device__ __forceinline__ void colmax_update(uint16_t* colmax, size_t idx, uint32_t mag)
+{
+    uint32_t* word = reinterpret_cast<uint32_t*>(colmax + (idx & ~size_t(1)));
+    const int sh = (idx & 1) ? 16 : 0;
+    uint32_t old = *word;
+    while (((old >> sh) & 0xFFFFu) < mag) {
+        const uint32_t want = (old & ~(0xFFFFu << sh)) | (mag << sh);
+        const uint32_t seen = atomicCAS(word, old, want);
+        if (seen == old) break;
+        old = seen;
+    }
+}
+
+__global__ __launch_bounds__(256) void append_block_kernel(akv_cache c, const uint16_t* __restrict__ k_new,
+                                                           const uint16_t* __restrict__ v_new,
+                                                           const int32_t* __restrict__ n_new, int n)
+{
+    __shared__ uint16_t tile[kTB][kTilePad];
+    __shared__ int last_s;
+    const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int Hkv = c.shape.Hkv, Ncap = c.shape.Ncap, NB = Ncap / kTB;
+    const int len = c.lens[b];
+    int cnt = n_new ? n_new[b] : n;
+    cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
+    const bool fits = len + cnt <= Ncap;   // else the sequence is left unchanged and the refusal is counted
+    const int first_blk = len / kTB;
+    const int touched = cnt > 0 ? (len % kTB + cnt + kTB - 1) / kTB : 0;   // K blocks the new tokens fall into
+    const int nwg = fits ? touched : (cnt > 0 ? 1 : 0);                    // workgroups per head that have work (or count the refusal)
+    if ((int)blockIdx.x >= nwg) return;
+    const size_t bh = size_t(b) * Hkv + h;
+    if (fits) {
+        const int blk = first_blk + blockIdx.x;
+        const int t_lo = max(len, blk * kTB), t_hi = min(len + cnt, (blk + 1) * kTB);   // tokens of this block: [t_lo, t_hi)
+        const uint16_t* kn = k_new + bh * n * kD;   // row i of the input is token len + i
+        const uint16_t* vn = v_new + bh * n * kD;
+        // ---- V: thread -> (row, 16 channels), 16 rows per pass ----
+        for (int t = t_lo + (tid >> 3); t < t_hi; t += 32) {
+            const int cl = tid & 7;
+            const uint4* src = reinterpret_cast<const uint4*>(vn + size_t(t - len) * kD + cl * 16);
+            const uint4 x0 = src[0], x1 = src[1];
+            const uint32_t w[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};   // word i: channels 2i (low half), 2i+1
+            uint32_t hi[4] = {0, 0, 0, 0}, mid[2] = {0, 0}, lo[2] = {0, 0};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t e0 = w[i] & 0xFFFFu, e1 = w[i] >> 16;
+                hi[i / 2] |= ((e0 >> 8) | ((e1 >> 8) << 8)) << (16 * (i & 1));
+                mid[i / 4] |= (((e0 >> 4) & 15u) | (((e1 >> 4) & 15u) << 4)) << (8 * (i & 3));
+                lo[i / 4] |= ((e0 & 15u) | ((e1 & 15u) << 4)) << (8 * (i & 3));
+            }
+            const size_t row = bh * Ncap + t;
+            *reinterpret_cast<uint4*>(c.v_hi + row * kD + cl * 16) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *reinterpret_cast<uint2*>(c.v_mid + row * (kD / 2) + cl * 8) = make_uint2(mid[0], mid[1]);
+            *reinterpret_cast<uint2*>(c.v_lo + row * (kD / 2) + cl * 8) = make_uint2(lo[0], lo[1]);
+        }
+        // ---- K ----
+        if (t_hi - t_lo == kTB) {   // the whole block: through the LDS tile
+            for (int idx = tid; idx < kTB * (kD / 8); idx += 256) {   // 16-byte pieces of the input rows
+                const int j = idx / (kD / 8), p8 = idx % (kD / 8);
+                const uint4 x = *reinterpret_cast<const uint4*>(kn + size_t(t_lo - len + j) * kD + p8 * 8);
+                uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[j][p8 * 8]);   // rows start at even halves: word aligned
+                dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+            }
+            __syncthreads();
+            const size_t colbase = (bh * NB + blk) * kD;
+            for (int idx = tid; idx < kD * (kTB / 16); idx += 256) {   // HI: (column d, 16 tokens) -> 16 bytes
+                const int d = idx / (kTB / 16), j0 = (idx % (kTB / 16)) * 16;
+                uint32_t o[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[i / 4] |= uint32_t(tile[j0 + i][d] >> 8) << (8 * (i & 3));
+                *reinterpret_cast<uint4*>(c.k_hi + (colbase + d) * kTB + j0) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+            for (int idx = tid; idx < kD * (kTB / 32); idx += 256) {   // MID, LO: (column d, 32 tokens) -> 16 bytes each
+                const int d = idx / (kTB / 32), j0 = (idx % (kTB / 32)) * 32;
+                uint32_t m[4] = {0, 0, 0, 0}, l[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t e0 = tile[j0 + 2 * i][d], e1 = tile[j0 + 2 * i + 1][d];
+                    m[i / 4] |= (((e0 >> 4) & 15u) | (((e1 >> 4) & 15u) << 4)) << (8 * (i & 3));
+                    l[i / 4] |= ((e0 & 15u) | ((e1 & 15u) << 4)) << (8 * (i & 3));
+                }
+                *reinterpret_cast<uint4*>(c.k_mid + (colbase + d) * (kTB / 2) + j0 / 2) = make_uint4(m[0], m[1], m[2], m[3]);
+                *reinterpret_cast<uint4*>(c.k_lo + (colbase + d) * (kTB / 2) + j0 / 2) = make_uint4(l[0], l[1], l[2], l[3]);
+            }
+            if (tid < kD) {
+                uint32_t mag = 0;
+                for (int j = 0; j < kTB; ++j) mag = max(mag, uint32_t(tile[j][tid]) & 0x7FFFu);
+                colmax_update(c.colmax, bh * kD + tid, mag);
+            }
+        } else if (tid < kD) {      // part of a block: token by token, thread d owns column d
+            uint32_t mag = 0;
+            for (int t = t_lo; t < t_hi; ++t) {
+                const uint32_t kx = kn[size_t(t - len) * kD + tid];
+                const int j = t % kTB;
+                const size_t col = (bh * NB + blk) * kD + tid;
+                c.k_hi[col * kTB + j] = (uint8_t)(kx >> 8);
+                const size_t nib = col * (kTB / 2) + j / 2;
+                const uint32_t om = c.k_mid[nib], ol = c.k_lo[nib];
+                if (j & 1) {
+                    c.k_mid[nib] = (uint8_t)((om & 0x0F) | (((kx >> 4) & 15u) << 4));
+                    c.k_lo[nib] = (uint8_t)((ol & 0x0F) | ((kx & 15u) << 4));
+                } else {
+                    c.k_mid[nib] = (uint8_t)((om & 0xF0) | ((kx >> 4) & 15u));
+                    c.k_lo[nib] = (uint8_t)((ol & 0xF0) | (kx & 15u));
+                }
+                mag = max(mag, kx & 0x7FFFu);
+            }
+            colmax_update(c.colmax, bh * kD + tid, mag);
+        }
+    }
+    // The workgroup of the sequence that arrives last (every one has read lens[b] by then) moves the length.
+    __syncthreads();
+    if (tid == 0) last_s = atomicAdd(&c.flags[AKV_NFLAGS + b], 1) == nwg * Hkv - 1;
+    __syncthreads();
+    if (last_s && tid == 0) {
+        c.flags[AKV_NFLAGS + b] = 0;
+        if (fits) c.lens[b] = len + cnt;
+        else atomicAdd(&c.flags[AKV_FLAG_OVERFLOW], 1);
+    }
+}
+
 hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
                          hipStream_t st)
 {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(append_kernel, dim3(c.shape.Hkv, c.shape.B), dim3(128), 0, st, c, k_new, v_new, n_new, n);
+    if (n < 32) {   // a few tokens: one workgroup per (sequence, KV head) walks them
+        hipLaunchKernelGGL(append_kernel, dim3(c.shape.Hkv, c.shape.B), dim3(128), 0, st, c, k_new, v_new, n_new, n);
+    } else {        // prefill: a workgroup per K block; n tokens touch at most n / 256 + 2 blocks
+        hipLaunchKernelGGL(append_block_kernel, dim3(n / kTB + 2, c.shape.Hkv, c.shape.B), dim3(256), 0, st, c, k_new, v_new, n_new, n);
+    }
     return hipGetLastError();
 }
 

@@ -73,6 +73,26 @@ def test_append_token_by_token_and_capacity_flag(T):
     T.assert_cache_equal(gc, oc)
 
 
+def test_append_prefill_after_unaligned_lengths(T):
+    """A long append onto sequences that end inside a K block: a partly covered first block, whole blocks through the
+    transposing path, a partly covered last block, ragged counts, K_colmax merged with what was there."""
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    say("append: prefill of up to 900 tokens after lengths 100 / 255 / 256 / 513")
+    B, Hkv, Ncap = 4, 2, 1536
+    k, v = workloads.edge_patterns(B, Hkv, 1500, seed=23)
+    lens0 = [100, 255, 256, 513]
+    oc = T.oracle_cache(k[:, :, :513], v[:, :, :513], lens0, Ncap)
+    gc = T.gpu_cache(k[:, :, :513], v[:, :, :513], lens0, 2, Ncap)
+    n_new = np.array([900, 770, 512, 300], np.int32)
+    kn, vn = k[:, :, 600:1500].contiguous(), v[:, :, 600:1500].contiguous()
+    assert O.append(oc, T.bits(kn), T.bits(vn), n_new) == 0
+    A.akv_append(gc, kn.to(DEV), vn.to(DEV), torch.from_numpy(n_new).to(DEV))
+    torch.cuda.synchronize()
+    T.assert_cache_equal(gc, oc)
+    assert not gc.flags.cpu().any()
+
+
 # ------------------------------------------------------------------------------------------ decode parity
 
 CASES = [

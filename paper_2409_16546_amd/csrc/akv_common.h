@@ -272,6 +272,22 @@ __device__ __forceinline__ int score_a(float x)
     return fl < (float)kAMin ? kAMin : (int)fl;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave in the vector ALU (six data-parallel-primitive steps: shifts by
+// 1, 2, 4, 8 inside the rows of 16 lanes, then lane 15 of a row added to the next row, then lane 31 to the upper
+// half); a lane without a source adds zero.
+__device__ __forceinline__ int wave_scan_add(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+// value of lane `l` (wave-uniform index) in every lane
+__device__ __forceinline__ int wave_read(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+
 __device__ __forceinline__ float wave_max(float v)
 {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));

@@ -134,11 +134,7 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
             mid_find_cut(c, kloc, J, below);   // the slice's own cut: never earlier than the sequence's
             const int fromcut = kloc - below;
             {   // running sums over the buckets, for the workgroup that merges the slices
-                int incl = c;
-                for (int o = 1; o < 64; o <<= 1) {
-                    const int u = __shfl_up(incl, o);
-                    if (lane >= o) incl += u;
-                }
+                const int incl = wave_scan_add(c);
                 int32_t* dst = a.hist + (hq * S + slice) * kHistStride;
                 store_agent(&dst[lane], incl);                      // tokens in buckets 0..lane
                 if (lane == 63) store_agent(&dst[64], in_slice);    // all tokens of the slice
@@ -198,7 +194,7 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
             }
             const uint64_t reached = __ballot(tot >= kk);
             const int J = reached ? __builtin_ctzll(reached) : 64;   // bucket 64 is the cut only if none before it is
-            const int below = J == 0 ? 0 : __shfl(tot, J - 1);
+            const int below = J == 0 ? 0 : wave_read(tot, J - 1);
             const int fromcut = kk - below;
             // slices that hold selected tokens, with the number of tokens of each kind before them: lane = slice
             int nlist = 0, carry_lt = 0, carry_eq = 0;
@@ -210,14 +206,7 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                     c_le = load_agent(&hist[s * kHistStride + J]);
                 }
                 const int c_eq = c_le - c_lt;
-                int i_lt = c_lt, i_eq = c_eq;   // inclusive scan over the lanes
-                for (int o = 1; o < 64; o <<= 1) {
-                    const int u_lt = __shfl_up(i_lt, o), u_eq = __shfl_up(i_eq, o);
-                    if (lane >= o) {
-                        i_lt += u_lt;
-                        i_eq += u_eq;
-                    }
-                }
+                const int i_lt = wave_scan_add(c_lt), i_eq = wave_scan_add(c_eq);   // inclusive over the lanes
                 const int p_lt = carry_lt + i_lt - c_lt, p_eq = carry_eq + i_eq - c_eq;   // exclusive prefixes
                 const bool holds = c_lt > 0 || (c_eq > 0 && p_eq < fromcut);
                 const uint64_t hb = __ballot(holds);   // at most kk such slices in all: each holds a selected token
@@ -228,8 +217,8 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                     list_eq[wave][at] = p_eq;
                 }
                 nlist += __builtin_popcountll(hb);
-                carry_lt += __shfl(i_lt, 63);
-                carry_eq += __shfl(i_eq, 63);
+                carry_lt += wave_read(i_lt, 63);
+                carry_eq += wave_read(i_eq, 63);
             }
             // ---- the selection out of those slices' candidates: lane = candidate (token order inside a slice) ------
             constexpr int kAhead = 8;   // slices of the list whose candidates are in flight

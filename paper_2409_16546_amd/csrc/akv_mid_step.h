@@ -37,15 +37,10 @@ __device__ __forceinline__ void mid_emit(MidShared& sm, int set, int pos, int t,
 // none before it is): first bucket J where the running count reaches kk, and the number of tokens in buckets below it.
 __device__ __forceinline__ void mid_find_cut(int c, int kk, int& J, int& below)
 {
-    const int lane = threadIdx.x & 63;
-    int incl = c;
-    for (int o = 1; o < 64; o <<= 1) {
-        const int u = __shfl_up(incl, o);
-        if (lane >= o) incl += u;
-    }
+    const int incl = wave_scan_add(c);
     const uint64_t reached = __ballot(incl >= kk);
     J = reached ? __builtin_ctzll(reached) : 64;
-    below = J == 0 ? 0 : __shfl(incl, J - 1);
+    below = J == 0 ? 0 : wave_read(incl, J - 1);
 }
 
 // tokens of each kind in lower lanes of the wave (token order = lane, then i), and in the whole wave
@@ -86,11 +81,11 @@ __device__ __forceinline__ int mid_select_chunk(MidShared& sm, int set, const fl
     int J, below;
     mid_find_cut(tot, kk, J, below);
     const int fromcut = kk - below;
-    int base_lt = lane < J ? before : 0;   // selected-for-sure tokens in earlier waves: buckets < J
-    for (int o = 1; o < 64; o <<= 1) base_lt += __shfl_xor(base_lt, o);
-    int base_eq;                            // tokens of the cut bucket in earlier waves
+    // selected-for-sure tokens in earlier waves: buckets < J; tokens of the cut bucket in earlier waves
+    const int base_lt = wave_read(wave_scan_add(lane < J ? before : 0), 63);
+    int base_eq;
     if (J < 64) {
-        base_eq = __shfl(before, J);
+        base_eq = wave_read(before, J);
     } else {
         base_eq = 0;
         for (int w = 0; w < wave; ++w) base_eq += sm.cntw[w][64];

@@ -288,10 +288,26 @@ __device__ __forceinline__ int wave_scan_add(int v)
 // value of lane `l` (wave-uniform index) in every lane
 __device__ __forceinline__ int wave_read(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
 
+// maximum over the 64 lanes of a wave, in every lane: the steps of wave_scan_add with max (a lane without a source
+// keeps its value), then lane 63 holds the maximum of all
 __device__ __forceinline__ float wave_max(float v)
 {
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    auto step = [](float x, int ctrl_sel) {
+        const int xi = __builtin_bit_cast(int, x);
+        int yi;
+        switch (ctrl_sel) {
+            case 0: yi = __builtin_amdgcn_update_dpp(xi, xi, 0x111, 0xF, 0xF, false); break;
+            case 1: yi = __builtin_amdgcn_update_dpp(xi, xi, 0x112, 0xF, 0xF, false); break;
+            case 2: yi = __builtin_amdgcn_update_dpp(xi, xi, 0x114, 0xF, 0xF, false); break;
+            case 3: yi = __builtin_amdgcn_update_dpp(xi, xi, 0x118, 0xF, 0xF, false); break;
+            case 4: yi = __builtin_amdgcn_update_dpp(xi, xi, 0x142, 0xA, 0xF, false); break;
+            default: yi = __builtin_amdgcn_update_dpp(xi, xi, 0x143, 0xC, 0xF, false); break;
+        }
+        return fmaxf(x, __builtin_bit_cast(float, yi));
+    };
+#pragma unroll
+    for (int k = 0; k < 6; ++k) v = step(v, k);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ int wave_sum_int(int v)
 {

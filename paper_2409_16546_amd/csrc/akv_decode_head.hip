@@ -81,7 +81,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     // The HI bytes of the wave's first block do not depend on the levels: they go in flight behind the loads of
     // the level computation (issued at the top of the kernel) and arrive while it runs.
     const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-    u32x4_t kpre[4] = {zero4, zero4, zero4, zero4};
+    u32x4_t kpre[6] = {zero4, zero4, zero4, zero4, zero4, zero4};
     const bool pre_any = blk < blk_end;
     if (pre_any) k_tile_pre(a, b, h, blk, kpre);
     const uint32_t colmax_used = k_levels_finish<G>(a, b, h, ks, true, k_new_bits, lin);

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
     if (blk * kTB < len) {                       // else this wave's block is beyond the sequence
         float tm[G];
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-        const u32x4_t none[4] = {zero4, zero4, zero4, zero4};
+        const u32x4_t none[6] = {zero4, zero4, zero4, zero4, zero4, zero4};
         float lg[G][4];
         k_tile<G>(a, b, h, blk, len, ks, 0, tm, none, false, lg, &kstage[wave_u][0]);
         if (lane == 0)

@@ -146,20 +146,20 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v)
 constexpr int kKU = 8;            // columns per group
 constexpr int kKStage = 4096;     // bytes of LDS staging per wave
 
-// HI bytes of the first two groups of a tile, issued before the levels are known (they are always read):
+// HI bytes of the first three groups of a tile, issued before the levels are known (they are always read):
 // pre[] is handed to k_tile (use_pre = true) for the same block.
-__device__ __forceinline__ void k_tile_pre(const DecodeArgs& a, int b, int h, int blk, u32x4_t (&pre)[4])
+__device__ __forceinline__ void k_tile_pre(const DecodeArgs& a, int b, int h, int blk, u32x4_t (&pre)[6])
 {
     const int lane = threadIdx.x & 63;
     const size_t bh = size_t(b) * a.s.Hkv + h;
     const __amdgpu_buffer_rsrc_t rh = make_rsrc(a.k_hi + (bh * a.s.Ncap + size_t(blk) * kTB) * kD, uint32_t(kTB) * kD);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) pre[i] = buf_load_b128(rh, uint32_t(lane) * 16 + i * 1024);
+    for (int i = 0; i < 6; ++i) pre[i] = buf_load_b128(rh, uint32_t(lane) * 16 + i * 1024);
 }
 
 template <int G>
 __device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int blk, int len, const KShared<G>& ks,
-                                       int aux, float (&tile_max)[G], const u32x4_t (&pre)[4], bool use_pre,
+                                       int aux, float (&tile_max)[G], const u32x4_t (&pre)[6], bool use_pre,
                                        float (&acc)[G][4], uint8_t* stage)
 {
     constexpr int U = kKU;
@@ -244,27 +244,32 @@ __device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int bl
         }
         __builtin_amdgcn_wave_barrier();
     };
-    // three groups rotate by name: two are in flight (8 KB per wave) while one is consumed
+    // three groups rotate by name: all three are issued before the first is consumed, and a group is issued again
+    // as soon as it has been consumed (8 to 12 KB in flight per wave)
     Group A, B, C;
-    if (use_pre) {   // uniform: the HI bytes of the first two groups are already in flight (k_tile_pre)
+    if (use_pre) {   // uniform: the HI bytes of the first three groups are already in flight (k_tile_pre)
         A.h0 = pre[0];
         A.h1 = pre[1];
         B.h0 = pre[2];
         B.h1 = pre[3];
+        C.h0 = pre[4];
+        C.h1 = pre[5];
         issue_nib(A, 0);
         issue_nib(B, U);
+        issue_nib(C, 2 * U);
     } else {
         issue(A, 0);
         issue(B, U);
+        issue(C, 2 * U);
     }
 #pragma unroll 1
     for (int d0 = 0; d0 < kD; d0 += 3 * U) {
-        issue(C, d0 + 2 * U);
         compute(A, d0);
         issue(A, d0 + 3 * U);
         if (d0 + U < kD) compute(B, d0 + U);   // kD is not a multiple of 3 * U: the last round is partial
         issue(B, d0 + 4 * U);
         if (d0 + 2 * U < kD) compute(C, d0 + 2 * U);
+        issue(C, d0 + 5 * U);
     }
 
     // ---- logits out, tile maxima -----------------------------------------------------------------

@@ -4,7 +4,7 @@
 A step = one pass of the whole hot path over one batch: append one new token per sequence into the
 split-plane cache and decode attention (Rule 1 levels, q.K~ pass, mid step, Rule 2 + S.V~ pass, final
 division) for one query token per sequence -- one call of akv_append_decode_attention, one kernel.
-Workload: BASELINE config 2 (Llama-2-7B-shaped layer, batch 8, 32 heads, head_dim 128, context 4096,
+Workload: benchmark configuration 2 (Llama-2-7B-shaped layer, batch 8, 32 heads, head_dim 128, context 4096,
 synthetic fp16 K/V with per-channel log-uniform scales).  Inputs are resident in HBM before the timed
 region; the steps rotate over several cache copies so that no copy is still in the L2 / Infinity Cache
 when it is read again.  The tokens the steps append are the workload's own last tokens, so the last step

@@ -308,7 +308,7 @@ def test_append_decode_in_one_call_across_block_chunk_and_prefetch_boundaries(T,
 
 
 def test_cfg2_full_size_sampled_against_oracle(T):
-    """BASELINE config 2 at full size in the launch configuration bench.py times (max_len = N, no debug
+    """Benchmark configuration 2 at full size in the launch configuration bench.py times (max_len = N, no debug
     exports in the timed call); 6 sampled (sequence, head) pairs are recomputed by the oracle."""
     from paper_2409_16546_amd import workloads, binding as A
     from oracle import akv_oracle as O
@@ -340,7 +340,7 @@ def test_cfg2_full_size_sampled_against_oracle(T):
 
 @pytest.mark.parametrize("cfg", [3, 4, 5])
 def test_full_size_configs_3_to_5_sampled_against_oracle(T, cfg):
-    """BASELINE configs 3-5 at full size with the library's choice of path: config 3 (B16, MHA, 8192 tokens; the
+    """Benchmark configurations 3-5 at full size with the library's choice of path: config 3 (B16, MHA, 8192 tokens; the
     last token is appended inside the step) runs the head-per-workgroup kernel with two blocks per wave and two
     chunks in the mid step; configs 4 and 5 (GQA 32/8, 32768 tokens / ragged lengths up to 131072) run the
     token-split kernels.  Three sampled (sequence, KV head) pairs are recomputed by the oracle."""

@@ -115,7 +115,9 @@ typedef struct akv_params {
     int32_t guard_bits;   /* extra mantissa bits both rules require, 0..12 (0 = the literal rule)    */
     int32_t force_level;  /* -1 adaptive; 0/1/2 read everything at 8/12/16 bits (2 = control group)  */
     int32_t out_dtype;    /* 0: out is float32 [B][Hq][D]; 1: out is fp16 [B][Hq][D]                 */
-    int32_t max_len;      /* host-known upper bound of lens[] used to size the launch; 0 means Ncap  */
+    int32_t max_len;      /* host-known upper bound of lens[] used to size the launch; 0 means Ncap.
+                             A value below a sequence's length must not be passed: the token-split
+                             kernels then attend to the first max_len tokens only                   */
     const akv_debug *dbg; /* host pointer to a struct of device pointers, or NULL                    */
     void *const *events;  /* host pointer to 3 hipEvent_t, or NULL: the library records them on the
                              stream before its first kernel, between the K kernel and the V kernel of
@@ -206,9 +208,10 @@ akv_status akv_fp16_decode_attention(const akv_shape *shape, const uint16_t *k, 
  * Measurement aid: read `bytes` bytes (16-byte aligned, a multiple of 16) of
  * device memory at buf once with a plain streaming kernel and discard them.
  * Timed by a caller, it gives the read ceiling of the device that the decode
- * kernels' effective bandwidth is put beside ("memory access latency ... is
- * the bottleneck", the paper's premise).  sink: device uint32, never read,
- * practically never written.  Nothing is allocated; asynchronous on stream.
+ * kernels' effective bandwidth is put beside (decoding is bound by memory
+ * access, the premise of the paper's introduction).  sink: device uint32,
+ * never read, practically never written.  Nothing is allocated; asynchronous
+ * on stream.
  */
 akv_status akv_stream_read(const void *buf, size_t bytes, uint32_t *sink, void *stream);
 

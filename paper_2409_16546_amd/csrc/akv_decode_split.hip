@@ -24,7 +24,7 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
     const int h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63;
     const int Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
-    const int len = min(a.lens[b], Ncap);
+    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all three kernels
     const int wave_u = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int blk = blockIdx.x * kKWaves + wave_u;
     if (blockIdx.x * kMidSlice >= len) return;   // whole workgroup beyond the sequence (uniform)
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
     const int S = (Ncap + kMidSlice - 1) / kMidSlice;   // slices per query head in the workspace
-    const int len = min(a.lens[b], Ncap);
+    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all three kernels
     const size_t bh = size_t(b) * Hkv + h;
     if (slice * kMidSlice >= len) return;   // uniform; also every empty sequence
     const int nblk = (len + kTB - 1) / kTB, nsl = (len + kMidSlice - 1) / kMidSlice;
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane >> 3, cl = lane & 7;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
-    const int len = min(a.lens[b], Ncap);
+    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all three kernels
     const int vchunk = a.vchunk;   // tokens per workgroup: a multiple of kVChunk chosen at launch
     const int c0 = split * vchunk;
     const size_t bh = size_t(b) * Hkv + h;

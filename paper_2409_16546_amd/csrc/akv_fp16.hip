@@ -25,7 +25,7 @@ struct F16Args {
     const int32_t* lens;
     void* out;
     float c;   // scale * log2(e)
-    int out_dtype, nsplit;
+    int out_dtype, nsplit, max_len;
     float *partO, *partM, *partZ;
 };
 
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(64 * kFWaves) void fp16_kernel(F16Args a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane >> 4, cl = lane & 15;            // row within the wave's group of 4, channels 8*cl..8*cl+7
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
-    const int len = min(a.lens[b], Ncap);
+    const int len = min(min(a.lens[b], Ncap), a.max_len);
     const int c0 = split * kFChunk;
     if (c0 >= len) return;
     const size_t bh = size_t(b) * Hkv + h;
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(64 * kFWaves) void fp16_kernel(F16Args a)
 __global__ __launch_bounds__(kD) void fp16_combine_kernel(F16Args a)
 {
     const int hq_i = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-    const int len = min(a.lens[b], a.s.Ncap);
+    const int len = min(min(a.lens[b], a.s.Ncap), a.max_len);
     const size_t hq = size_t(b) * a.s.Hq + hq_i;
     const int used = (len + kFChunk - 1) / kFChunk;
     float M = -INFINITY;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane >> 4, cl = lane & 15;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
-    const int len = min(a.lens[b], Ncap);
+    const int len = min(min(a.lens[b], Ncap), a.max_len);
     if (len == 0) {
         for (int idx = tid; idx < G * kD; idx += NT) {
             const size_t o = (size_t(b) * Hq + size_t(h) * G) * kD + idx;
@@ -319,6 +319,7 @@ hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v,
     a.c = (float)((double)scale * 1.4426950408889634);
     a.out_dtype = out_dtype;
     a.nsplit = f_splits(s.Ncap);
+    a.max_len = max_len;
     const size_t bhq = size_t(s.B) * s.Hq;
     char* p = reinterpret_cast<char*>(ws);
     a.partO = reinterpret_cast<float*>(p);

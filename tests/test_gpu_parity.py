@@ -212,6 +212,48 @@ def test_max_len_hint_gives_the_same_result(T):
         assert torch.equal(o1, o2)
 
 
+def test_max_len_hint_below_a_length_leaves_the_library_in_order(T):
+    """A hint below a sequence's length is a caller's mistake; the token-split kernels then leave the tokens past it
+    out, and the next correct call must not see anything stale (tickets, partial results)."""
+    from paper_2409_16546_amd import workloads, binding as A
+    say("decode: max_len below a length, then a correct call (split path, adaptive and fp16)")
+    w = workloads.make(2, B=2, Hq=4, Hkv=2, N=3000)
+    lens = [3000, 1500]
+    gc = T.gpu_cache(w.k, w.v, lens, w.Hq, 4096)
+    q = w.q.to(DEV)
+    ref = A.akv_decode_attention(gc, q, path=2).clone()
+    short = A.akv_decode_attention(gc, q, max_len=1100, path=2).clone()
+    again = A.akv_decode_attention(gc, q, path=2).clone()
+    torch.cuda.synchronize()
+    assert torch.isfinite(short.float()).all()
+    assert torch.equal(ref, again)
+    ku, vu = A.akv_unpack(gc)
+    lens_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    f_ref = A.akv_fp16_decode_attention(ku, vu, lens_d, q).clone()
+    f_short = A.akv_fp16_decode_attention(ku, vu, lens_d, q, max_len=1100).clone()
+    f_again = A.akv_fp16_decode_attention(ku, vu, lens_d, q).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(f_ref, f_again)
+    # the fp16 kernels with the short hint attend to exactly the first 1100 tokens
+    f_cut = A.akv_fp16_decode_attention(ku, vu, torch.tensor([1100, 1100], dtype=torch.int32, device=DEV), q)
+    torch.cuda.synchronize()
+    assert torch.equal(f_short, f_cut)
+
+
+def test_stream_read_runs_and_checks_its_arguments(T):
+    from paper_2409_16546_amd import binding as A
+    say("stream read: 64 MiB + ragged tail, misaligned size refused")
+    buf = torch.zeros((64 << 20) + 48, dtype=torch.uint8, device=DEV)
+    sink = torch.zeros(1, dtype=torch.int32, device=DEV)
+    A.akv_stream_read(buf, sink)
+    A.akv_stream_read(buf[:16], sink)
+    torch.cuda.synchronize()
+    assert int(sink.cpu()[0]) == 0
+    with pytest.raises(A.AkvError) as e:
+        A.akv_stream_read(buf[:24], sink)
+    assert e.value.status == A.AKV_EINVAL
+
+
 def test_bad_arguments_are_refused_on_the_host(T):
     from paper_2409_16546_amd import binding as A
     say("errors: bad shape / params / workspace -> status codes, nothing launched")

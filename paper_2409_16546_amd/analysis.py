@@ -6,7 +6,11 @@ Data: the generator of the chosen benchmark configuration at a reduced batch / h
 head).  For every context length it prints the average number of bits read per K element and per V element (by
 the exported masks), and the relative error |R - R16| / |R16| of the logits and of the attention output against
 the same kernel reading all 16 bits, for the aligned cache (guard 0, 1, 2) and for uniform truncation to 12 and
-to 8 bits (force_level 1 and 0)."""
+to 8 bits (force_level 1 and 0).
+
+A second table estimates what a finer granule of the K rule would save: Rule 1 evaluated with a column maximum per
+256-token block instead of one per sequence ("Quantization of K-Cache": the columns are only roughly uniform along
+the tokens).  This is an estimate of bytes from the data, computed here in torch; no kernel reads K that way."""
 from __future__ import annotations
 
 import argparse
@@ -23,6 +27,25 @@ def rel_err(x: torch.Tensor, ref: torch.Tensor) -> np.ndarray:
     x = x.double().flatten()
     keep = ref != 0
     return ((x[keep] - ref[keep]).abs() / ref[keep].abs()).cpu().numpy()
+
+
+def bits_k_with_block_colmax(k: torch.Tensor, q: torch.Tensor, n: int, guard_bits: int, block: int) -> float:
+    """Average bits per K element over the first n tokens if Rule 1 took its column maxima per `block` tokens
+    (block >= n: one maximum per sequence, the rule the kernels implement).  k: [B, H, N, D] fp16, q: [B, H, D] fp16."""
+    kk = k[:, :, :n].float().abs()
+    B, H, _, D = kk.shape
+    total, weight = 0.0, 0
+    for t0 in range(0, n, block):
+        t1 = min(n, t0 + block)
+        cm = kk[:, :, t0:t1].amax(dim=2).clamp_min(2.0 ** -14)          # [B, H, D]
+        P = q.float() * cm                                                 # exact in fp32 (11-bit x 11-bit mantissas)
+        e = torch.frexp(P)[1].float()
+        e = torch.where(P != 0, e, torch.full_like(e, -1e9))
+        m = 10 + guard_bits - (e.amax(dim=-1, keepdim=True) - e)
+        lvl = torch.where(P != 0, (m > 2).float() + (m > 6).float(), torch.zeros_like(m))
+        total += float((8 + 4 * lvl).sum()) * (t1 - t0)
+        weight += B * H * D * (t1 - t0)
+    return total / weight
 
 
 def main() -> None:
@@ -61,6 +84,14 @@ def main() -> None:
             print(f"| {n} | {name} | {bits_k:.2f} | {bits_v:.2f} | {np.median(el):.1e} / {np.percentile(el, 99):.1e} | "
                   f"{np.median(eo):.1e} / {np.percentile(eo, 99):.1e} | {rl2:.1e} |", flush=True)
         del c, dbg
+    print()
+    print("| context | guard | bits K, one colmax per sequence | bits K, one colmax per 256-token block | per 64-token block |")
+    print("|---|---|---|---|---|")
+    for n in args.lengths:
+        for g in (0, 1, 2):
+            whole = bits_k_with_block_colmax(kd, qd, n, g, 1 << 30)
+            print(f"| {n} | {g} | {whole:.2f} | {bits_k_with_block_colmax(kd, qd, n, g, 256):.2f} | "
+                  f"{bits_k_with_block_colmax(kd, qd, n, g, 64):.2f} |", flush=True)
 
 
 if __name__ == "__main__":

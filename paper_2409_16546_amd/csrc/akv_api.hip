@@ -133,6 +133,36 @@ akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, 
 namespace {
 
 // decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])
+// compute units of the current device (256 on MI355X), looked up once
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+        else cus = 256;
+    }
+    return cus;
+}
+
+// Head-per-workgroup or token-split kernels, when the caller leaves the choice to the library.  One head kernel
+// workgroup occupies a compute unit, so `pairs` (sequence, KV head) pairs run in ceil(pairs / CUs) rounds of equal
+// length: the path pays when those rounds are (nearly) full, or when the sequences are so short that the single
+// launch outweighs idle units.  The thresholds are where the two paths crossed when timed over pairs = 64..1024,
+// lengths 1024..16384 and group sizes 1, 2, 4 on MI355X.
+bool head_path_pays(long pairs, int G, int max_len)
+{
+    if (max_len > 16384) return false;
+    const long cus = compute_units();
+    const long rounds = (pairs + cus - 1) / cus;
+    const double fill = double(pairs) / double(rounds * cus);
+    if (rounds == 1) {
+        if (pairs >= 64 && max_len <= (G == 1 ? 2048 : 1024)) return true;
+        return fill >= (G == 4 ? 0.9 : 0.72);
+    }
+    return G == 1 && fill >= 0.9 && max_len >= 2048;
+}
+
 akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, void* out,
                        const akv_params* params, void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -168,12 +198,7 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     {   // V kernel of the token-split path: one round of workgroups that fills the device -- the tokens of a
         // (sequence, KV head) pair are cut into as many chunks as there are resident workgroups per pair, so that
         // the fixed costs per workgroup (Rule 2 constants, pipeline start, partial results) are paid once per slot
-        static int cus = 0;
-        if (cus == 0) {
-            int dev = 0, n = 0;
-            if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
-            else cus = 256;
-        }
+        const int cus = compute_units();
         const int G = a.s.Hq / a.s.Hkv;
         const int per_cu = G <= 1 ? 4 : (G <= 4 ? 3 : 1);   // resident V workgroups per compute unit (register budget)
         const long pairs = long(a.s.B) * a.s.Hkv;
@@ -201,9 +226,8 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     if (p.path < 0 || p.path > 2) return fail(AKV_EINVAL, "path = %d out of range 0..2", p.path);
     if (p.path == 1 && !akv::head_path_supported(a.s))
         return fail(AKV_EINVAL, "path 1 (head per workgroup) needs Hq/Hkv <= 4");
-    // enough (sequence, KV head) pairs to fill the 256 compute units -> one workgroup per pair
     const bool head_path = p.path == 1 || (p.path == 0 && akv::head_path_supported(a.s) &&
-                                           a.s.B * a.s.Hkv >= 192 && a.max_len <= 16384);
+                                           head_path_pays(long(a.s.B) * a.s.Hkv, a.s.Hq / a.s.Hkv, a.max_len));
     hipStream_t s = static_cast<hipStream_t>(stream);
     auto ev = [&](int i) -> hipEvent_t { return p.events ? static_cast<hipEvent_t>(p.events[i]) : nullptr; };
     if (p.events)

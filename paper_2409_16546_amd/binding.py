@@ -1,4 +1,4 @@
-"""ctypes binding of the C ABI in ``include/akv.h`` -- argument marshalling only.
+"""ctypes binding of the C ABI in ``include/akv.h`` and ``include/akw.h`` -- argument marshalling only.
 
 Every function has the name of its C entry point and hands torch device pointers and the current
 HIP stream to it; no step of the path runs here.  If ``libakv.so`` has not been built the import of
@@ -20,7 +20,9 @@ AKV_TB = 256
 AKV_NFLAGS = 4
 AKV_MAX_TOPK = 64
 EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
-           "akv_decode_attention", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read"]
+           "akv_decode_attention", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read",
+           "akw_layout_sizes", "akw_workspace_init", "akw_pack", "akw_unpack", "akw_gemv"]
+AKW_MAX_B = 4
 
 
 class AkvError(RuntimeError):
@@ -51,6 +53,18 @@ class akv_params(C.Structure):
     _fields_ = [("scale", C.c_float), ("topk", C.c_int32), ("guard_bits", C.c_int32), ("force_level", C.c_int32),
                 ("out_dtype", C.c_int32), ("max_len", C.c_int32), ("dbg", C.POINTER(akv_debug)),
                 ("events", C.POINTER(C.c_void_p)), ("path", C.c_int32)]
+
+
+class akw_weights(C.Structure):
+    _fields_ = [("K", C.c_int32), ("N", C.c_int32)] + [(n, C.c_void_p) for n in ("hi", "mid", "lo", "rowmax")]
+
+
+class akw_sizes(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("hi", "mid", "lo", "rowmax", "workspace")]
+
+
+class akw_params(C.Structure):
+    _fields_ = [("guard_bits", C.c_int32), ("force_level", C.c_int32), ("lvl_out", C.c_void_p)]
 
 
 _lib = None
@@ -88,6 +102,17 @@ def lib() -> C.CDLL:
         L.akv_fp16_decode_attention.argtypes = [C.POINTER(akv_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                 C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
                                                 C.c_void_p]
+        L.akw_layout_sizes.restype = C.c_int
+        L.akw_layout_sizes.argtypes = [C.c_int32, C.c_int32, C.POINTER(akw_sizes)]
+        L.akw_workspace_init.restype = C.c_int
+        L.akw_workspace_init.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.akw_pack.restype = C.c_int
+        L.akw_pack.argtypes = [C.POINTER(akw_weights), C.c_void_p, C.c_void_p]
+        L.akw_unpack.restype = C.c_int
+        L.akw_unpack.argtypes = [C.POINTER(akw_weights), C.c_void_p, C.c_void_p]
+        L.akw_gemv.restype = C.c_int
+        L.akw_gemv.argtypes = [C.POINTER(akw_weights), C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(akw_params), C.c_void_p,
+                               C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -279,3 +304,69 @@ def akv_fp16_decode_attention(k: torch.Tensor, v: torch.Tensor, lens: torch.Tens
                                            0 if out.dtype == torch.float32 else 1, max_len, _ptr(workspace),
                                            workspace.numel(), _stream()))
     return out
+
+
+# ------------------------------------------------------------------------------------------ weight GEMV (akw.h)
+
+def akw_layout_sizes(K: int, N: int) -> akw_sizes:
+    out = akw_sizes()
+    _check(lib().akw_layout_sizes(K, N, C.byref(out)))
+    return out
+
+
+@dataclass
+class Weights:
+    """Caller-owned device buffers of one weight matrix in split planes (torch owns the memory)."""
+    K: int
+    N: int
+    hi: torch.Tensor = field(repr=False, default=None)
+    mid: torch.Tensor = field(repr=False, default=None)
+    lo: torch.Tensor = field(repr=False, default=None)
+    rowmax: torch.Tensor = field(repr=False, default=None)
+    workspace: torch.Tensor = field(repr=False, default=None)
+
+    @staticmethod
+    def allocate(K: int, N: int, device="cuda:0") -> "Weights":
+        sz = akw_layout_sizes(K, N)
+        u8 = lambda n: torch.empty(n, dtype=torch.uint8, device=device)
+        w = Weights(K, N, u8(sz.hi), u8(sz.mid), u8(sz.lo), torch.empty(K, dtype=torch.int16, device=device),
+                    u8(sz.workspace))
+        akw_workspace_init(w, w.workspace)
+        return w
+
+    def struct(self) -> akw_weights:
+        return akw_weights(self.K, self.N, _ptr(self.hi), _ptr(self.mid), _ptr(self.lo), _ptr(self.rowmax))
+
+
+def akw_workspace_init(w: Weights, workspace: torch.Tensor) -> None:
+    _check(lib().akw_workspace_init(w.K, w.N, _ptr(workspace), workspace.numel(), _stream()))
+
+
+def akw_pack(w: Weights, W: torch.Tensor) -> None:
+    """W: fp16 [K, N] on the device."""
+    assert W.dtype == torch.float16 and tuple(W.shape) == (w.K, w.N)
+    s = w.struct()
+    _check(lib().akw_pack(C.byref(s), _ptr(W), _stream()))
+
+
+def akw_unpack(w: Weights) -> torch.Tensor:
+    out = torch.empty(w.K, w.N, dtype=torch.float16, device=w.hi.device)
+    s = w.struct()
+    _check(lib().akw_unpack(C.byref(s), _ptr(out), _stream()))
+    return out
+
+
+def akw_gemv(w: Weights, x: torch.Tensor, y: torch.Tensor | None = None, *, guard_bits: int = 0, force_level: int = -1,
+             lvl_out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """x: fp16 [B, K] on the device; returns y: float32 [B, N].  lvl_out: uint8 [K] receiving the row levels."""
+    assert x.dtype == torch.float16 and x.dim() == 2 and x.shape[1] == w.K
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty(B, w.N, dtype=torch.float32, device=x.device)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (B, w.N)
+    if lvl_out is not None:
+        assert lvl_out.dtype == torch.uint8 and lvl_out.numel() == w.K
+    ws = w.workspace if workspace is None else workspace
+    s, p = w.struct(), akw_params(guard_bits, force_level, _ptr(lvl_out))
+    _check(lib().akw_gemv(C.byref(s), _ptr(x), B, _ptr(y), C.byref(p), _ptr(ws), ws.numel(), _stream()))
+    return y

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libakv.so")
-SOURCES = ["akv_api.hip", "akv_append.hip", "akv_decode_split.hip", "akv_decode_head.hip", "akv_fp16.hip"]
+SOURCES = ["akv_api.hip", "akv_append.hip", "akv_decode_split.hip", "akv_decode_head.hip", "akv_fp16.hip", "akw_gemv.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                                   # the decision path is written op by op; FMAs are explicit

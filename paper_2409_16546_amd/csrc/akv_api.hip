@@ -46,6 +46,28 @@ akv_status hip_fail(hipError_t e, const char* what)
 
 }  // namespace
 
+namespace akv {
+// the same error record for the other entry points of the library
+akv_status fail_msg(akv_status st, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+        else cus = 256;
+    }
+    return cus;
+}
+}  // namespace akv
+
 extern "C" {
 
 int akv_version(void) { return 100; }
@@ -133,17 +155,7 @@ akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, 
 namespace {
 
 // decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])
-// compute units of the current device (256 on MI355X), looked up once
-int compute_units()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
-        else cus = 256;
-    }
-    return cus;
-}
+using akv::compute_units;
 
 // Head-per-workgroup or token-split kernels, when the caller leaves the choice to the library.  One head kernel
 // workgroup occupies a compute unit, so `pairs` (sequence, KV head) pairs run in ceil(pairs / CUs) rounds of equal

@@ -138,6 +138,8 @@ __device__ __forceinline__ uint32_t store_token(uint8_t* k_hi, uint8_t* k_mid, u
 }
 #endif
 
+akv_status fail_msg(akv_status st, const char* fmt, ...);   // records the text akv_last_error() returns
+int compute_units();                                         // of the current device (256 on MI355X), looked up once
 hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
                          hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);

@@ -110,3 +110,34 @@ def edge_patterns(B: int, Hkv: int, N: int, D: int = 128, seed: int = 7) -> tupl
         bits = torch.where(exp_all_ones, bits & ~0x0400, bits)  # Inf/NaN -> finite
         return bits.to(torch.uint16).view(torch.float16)
     return one(), one()
+
+
+# ---------------------------------------------------------------------------------------------- weight GEMV
+# The paper names the weights as the other operand its framework covers ("Precision Alignment in Uncertainty
+# Calculation") and measures nothing on them; the shapes below are the projection matrices of its model
+# (Llama-2-7B: hidden 4096, MLP 11008), the values are a stand-in: W ~ N(0, 1/K) times a per-row scale 10^U(-0.5, 0.5)
+# (the rows of a trained projection differ in norm), x ~ N(0, 1) with `outliers` channels x20 (a few activation
+# channels of a transformer carry values far above the rest).
+WEIGHT_SHAPES = {"attn_proj": (4096, 4096), "mlp_up": (4096, 11008), "mlp_down": (11008, 4096)}
+
+
+@dataclass
+class WeightWorkload:
+    name: str
+    K: int
+    N: int
+    W: torch.Tensor   # fp16 [K, N]
+    x: torch.Tensor   # fp16 [B, K]
+
+
+def make_weights(shape: str | tuple[int, int] = "attn_proj", B: int = 1, *, outliers: int = 8, seed: int = 2001) -> WeightWorkload:
+    K, N = WEIGHT_SHAPES[shape] if isinstance(shape, str) else shape
+    gen = torch.Generator().manual_seed(seed)
+    scale = torch.pow(10.0, torch.rand(K, 1, generator=gen) - 0.5) / (K ** 0.5)
+    W = _to_fp16(torch.randn(K, N, generator=gen, dtype=torch.float32) * scale)
+    x = torch.randn(B, K, generator=gen, dtype=torch.float32)
+    for b in range(B):
+        idx = torch.randperm(K, generator=gen)[:outliers]
+        x[b, idx] *= 20.0
+    return WeightWorkload(f"{shape} K{K} N{N} B{B} N(0,1/K) x row scales, x N(0,1) + {outliers} channels x20", K, N, W,
+                          _to_fp16(x))

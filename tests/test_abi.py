@@ -1,4 +1,4 @@
-"""The C-ABI library loads without a GPU and exports every symbol include/akv.h declares; host-only entry
+"""The C-ABI library loads without a GPU and exports every symbol include/akv.h and include/akw.h declare; host-only entry
 points (layout query, argument checks) behave as documented.  No compute call is made here."""
 import ctypes as C
 import os
@@ -19,9 +19,12 @@ def A():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "akv.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(akv_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("akv.h", "akw.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(ak[vw]_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_and_binding_name_the_same_entry_points(A):
@@ -53,8 +56,10 @@ def test_bad_shapes_are_refused_with_a_message(A, shape):
 def test_struct_layouts_match_the_header(A):
     # the binding's ctypes structs mirror the C structs field for field
     text = open(os.path.join(ROOT, "include", "akv.h")).read()
+    text += open(os.path.join(ROOT, "include", "akw.h")).read()
     for struct, cls in (("akv_shape", A.akv_shape), ("akv_sizes", A.akv_sizes), ("akv_cache", A.akv_cache),
-                        ("akv_debug", A.akv_debug), ("akv_params", A.akv_params)):
+                        ("akv_debug", A.akv_debug), ("akv_params", A.akv_params), ("akw_weights", A.akw_weights),
+                        ("akw_sizes", A.akw_sizes), ("akw_params", A.akw_params)):
         body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (struct, struct), text, flags=re.S).group(1)
         body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
         fields = []
@@ -66,3 +71,14 @@ def test_struct_layouts_match_the_header(A):
             first = names[0].split()[-1]
             fields += [first] + [n.strip() for n in names[1:]]
         assert fields == [f[0] for f in cls._fields_], struct
+
+
+def test_weight_layout_sizes_and_shape_checks(A):
+    sz = A.akw_layout_sizes(4096, 11008)
+    e = 4096 * 11008
+    assert (sz.hi, sz.mid, sz.lo, sz.rowmax) == (e, e // 2, e // 2, 4096 * 2)
+    assert sz.workspace % 256 == 0 and sz.workspace >= (4096 // 64) * 4 * 11008 * 4
+    for bad in ((4096, 11000), (4100, 4096), (0, 16), (65536, 32768)):
+        with pytest.raises(A.AkvError) as e_:
+            A.akw_layout_sizes(*bad)
+        assert e_.value.status == A.AKV_EINVAL and "bad shape" in str(e_.value)

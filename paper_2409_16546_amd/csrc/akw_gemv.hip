@@ -3,13 +3,15 @@
 // "A Framework for Aligning Precision" (Rule 1; an addend's bit width is its weight's), "Dynamic Quantization"
 // (first 8 / first 12 / all 16 bits, the rest counts as 100...).
 //
-// One kernel.  A workgroup (8 waves) owns 1024 columns x `slab` rows; lane -> 16 consecutive columns, so a row
-// costs a wave three vector-memory instructions whatever its level (16 B of HI, 8 B of MID, 8 B of LO per lane;
-// the planes that the level does not need are asked for out of range and fetch nothing).  Every workgroup derives
-// the largest addend exponent of each activation row from x and rowmax itself (K products, from L2) -- cheaper
-// than a launch of its own in front of a kernel that runs for a few microseconds; the HI bytes of its first rows
-// are in flight meanwhile.  The waves' sums meet in LDS, the slabs' sums in the workspace; the workgroup that
-// draws the last ticket of a column tile adds the slabs in slab order (the result does not depend on timing).
+// One kernel.  A workgroup (8 waves) owns a strip of 128 columns x 512 rows; a wave owns 64 of those rows, as
+// eight groups of 8 rows; lane -> row lane/8 of the group and the 16-column slice lane%8, so one 16-byte load per
+// lane fetches the 128 contiguous HI bytes of each of 8 rows (the MID and LO bytes: 8 bytes per lane; a row whose
+// level does not need a plane is asked for out of range and fetches nothing).  All of a wave's loads are in flight
+// at once: the HI bytes go first, before anything is known about the levels.  Every workgroup derives the largest
+// addend exponent of each activation row from x and rowmax itself (K products, from L2) -- cheaper than a launch
+// of its own in front of a kernel that runs for a few microseconds.  The sums over the 8 row lanes meet by lane
+// exchange, the waves' sums in LDS, the slabs' sums (K/512 of them) in the workspace: the workgroup that draws
+// the last ticket of a strip adds them in slab order, so the result does not depend on timing.
 #include <cstdarg>
 
 #include "../../include/akw.h"
@@ -19,66 +21,64 @@ namespace akv {
 
 constexpr int kWWaves = 8;                   // waves per workgroup
 constexpr int kWThreads = 64 * kWWaves;
-constexpr int kWCols = 1024;                 // columns per workgroup: 16 per lane
-constexpr int kWStep = 8;                    // rows a wave has in flight at a time
-constexpr int kWSlabMax = 256;               // rows per workgroup at most
+constexpr int kWCols = 128;                  // columns per workgroup: 16 per lane, 8 lanes per row
+constexpr int kWGroups = 8;                  // groups of 8 rows per wave
+constexpr int kWSlab = kWWaves * kWGroups * 8;   // rows per workgroup: 512
+static_assert(AKW_MAX_B * kWCols <= kWThreads && kWSlab == kWThreads, "a thread per (activation row, column) and per slab row");
 
 struct GemvArgs {
-    int K, N, slab, nslab;
+    int K, N, nslab;
     const uint8_t *hi, *mid, *lo;
     const uint16_t *rowmax, *x;
     float *y, *part;      // part: [nslab][B][N]
-    int32_t* count;       // [column tiles]
+    int32_t* count;       // [column strips]
     int guard_bits, force_level;
     uint8_t* lvl_out;
 };
 
-__host__ __device__ inline int gemv_slab_rows(int K, int N, int cus)
-{
-    const long tiles = (N + kWCols - 1) / kWCols;
-    int slab = 64;                                                  // 8 waves x 8 rows
-    while (slab < kWSlabMax && tiles * ((K + slab - 1) / slab) > 8L * cus) slab *= 2;
-    return slab;
-}
-
 template <int B>
-__global__ __launch_bounds__(kWThreads) void gemv_kernel(GemvArgs a)
+__global__ __launch_bounds__(kWThreads, 4) void gemv_kernel(GemvArgs a)   // two workgroups per compute unit at least
 {
     __shared__ int emax_s[B][kWWaves];
-    __shared__ int lvl_s[kWSlabMax];
-    __shared__ float xs[B][kWSlabMax];
-    __shared__ __align__(16) float red_s[kWWaves][kWCols];
+    __shared__ int lvl_s[kWSlab];
+    __shared__ float xs[B][kWSlab];
+    __shared__ float red_s[kWWaves][B][kWCols];
     __shared__ int last_s;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile = blockIdx.x, slab_i = blockIdx.y;
+    const int r = lane >> 3, cl = lane & 7;
+    const int strip = blockIdx.x, slab_i = blockIdx.y;
     const int K = a.K, N = a.N;
-    const int c0 = tile * kWCols, k0 = slab_i * a.slab;
-    const int nsteps = a.slab / (kWWaves * kWStep);
-    const bool lane_ok = c0 + lane * 16 < N;                        // N % 16 == 0: a lane is inside or outside as a whole
+    const int col = strip * kWCols + cl * 16, k0 = slab_i * kWSlab;
+    const bool lane_ok = col < N;                                   // N % 16 == 0: a lane is inside or outside as a whole
 
     const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.hi, uint32_t(K) * uint32_t(N));
     const __amdgpu_buffer_rsrc_t rs_mid = make_rsrc(a.mid, uint32_t(K) * uint32_t(N / 2));
     const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(a.lo, uint32_t(K) * uint32_t(N / 2));
-    auto row_of = [&](int s, int r) { return k0 + (s * kWWaves + wave) * kWStep + r; };
-    auto hi_off = [&](int k) { return lane_ok && k < K ? uint32_t(k) * uint32_t(N) + uint32_t(c0 + lane * 16) : kSkip; };
+    auto local_row = [&](int g) { return (wave * kWGroups + g) * 8 + r; };   // row of the slab this lane reads in group g
 
-    // ---- the wave's first rows: HI bytes in flight before anything is known about the levels
-    u32x4_t H[kWStep];
+    // ---- the wave's HI bytes: in flight before anything is known about the levels (asked for first: the sooner the
+    // stream of weights starts, the sooner it ends -- putting the few loads of the exponents in front of them
+    // measured slower)
+    u32x4_t H[kWGroups];
 #pragma unroll
-    for (int r = 0; r < kWStep; ++r) H[r] = buf_load_b128(rs_hi, hi_off(row_of(0, r)));
+    for (int g = 0; g < kWGroups; ++g) {
+        const int k = k0 + local_row(g);
+        H[g] = buf_load_b128(rs_hi, lane_ok && k < K ? uint32_t(k) * uint32_t(N) + uint32_t(col) : kSkip);
+    }
 
-    // ---- Rule 1: largest addend exponent of every activation row, over all K input features
+    // ---- Rule 1: largest addend exponent of every activation row, over all K input features (8 per thread and round)
     int emax[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) emax[b] = -1;
-    for (int v = tid; v < K / 8; v += kWThreads) {
+    const int nvec = K / 8;
+    for (int v = tid; v < nvec; v += kWThreads) {
         const uint4 rm = reinterpret_cast<const uint4*>(a.rowmax)[v];
         const uint32_t rw[4] = {rm.x, rm.y, rm.z, rm.w};
 #pragma unroll
         for (int b = 0; b < B; ++b) {
-            const uint4 xv = reinterpret_cast<const uint4*>(a.x)[size_t(b) * (K / 8) + v];
+            const uint4 xv = reinterpret_cast<const uint4*>(a.x)[size_t(b) * nvec + v];
             const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kWThreads) void gemv_kernel(GemvArgs a)
         if (lane == 0) emax_s[b][wave] = m;
     }
     __syncthreads();
-    if (tid < a.slab) {                                             // the slab's rows: level and activations
+    {                                                               // thread -> row k0 + tid of the slab: level and activations
         const int k = k0 + tid;
         int level = 0;
 #pragma unroll
@@ -114,101 +114,95 @@ __global__ __launch_bounds__(kWThreads) void gemv_kernel(GemvArgs a)
                     level = l > level ? l : level;
                 }
             }
-            xs[b][tid] = xf;
+            xs[b][tid] = xf;                                        // rows at or past K: 0
         }
         if (a.force_level >= 0) level = a.force_level;
         lvl_s[tid] = level;
-        if (a.lvl_out && tile == 0 && k < K) a.lvl_out[k] = (uint8_t)level;
+        if (a.lvl_out && strip == 0 && k < K) a.lvl_out[k] = (uint8_t)level;
     }
     __syncthreads();
 
-    // ---- the rows, kWStep at a time per wave
+    // ---- the planes the levels ask for, then the multiply-adds
+    u32x2_t M[kWGroups], L[kWGroups];
+    int lv[kWGroups];
+#pragma unroll
+    for (int g = 0; g < kWGroups; ++g) {
+        const int lr = local_row(g), k = k0 + lr;
+        lv[g] = lvl_s[lr];
+        const uint32_t off = uint32_t(k) * uint32_t(N / 2) + uint32_t(col / 2);
+        const bool in = lane_ok && k < K;
+        M[g] = buf_load_b64(rs_mid, in && lv[g] >= 1 ? off : kSkip);
+        L[g] = buf_load_b64(rs_lo, in && lv[g] >= 2 ? off : kSkip);
+    }
     float acc[B][16];
 #pragma unroll
     for (int b = 0; b < B; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
-#pragma unroll 1
-    for (int s = 0; s < nsteps; ++s) {
-        u32x2_t M[kWStep], L[kWStep];
-        int lv[kWStep];
-        if (s > 0) {
 #pragma unroll
-            for (int r = 0; r < kWStep; ++r) H[r] = buf_load_b128(rs_hi, hi_off(row_of(s, r)));
-        }
+    for (int g = 0; g < kWGroups; ++g) {
+        const uint32_t fill = fill_for_level(lv[g]);
+        uint32_t pa[4], pb[4];
+        assemble8_fill(H[g].x, H[g].y, M[g].x, L[g].x, fill, pa);   // columns 0..7 of the lane
+        assemble8_fill(H[g].z, H[g].w, M[g].y, L[g].y, fill, pb);   // columns 8..15
+        const float v[16] = {lo_half(pa[0]), lo_half(pa[1]), hi_half(pa[0]), hi_half(pa[1]),
+                             lo_half(pa[2]), lo_half(pa[3]), hi_half(pa[2]), hi_half(pa[3]),
+                             lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
+                             lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
+        const int lr = local_row(g);
 #pragma unroll
-        for (int r = 0; r < kWStep; ++r) {
-            const int k = row_of(s, r);
-            lv[r] = __builtin_amdgcn_readfirstlane(lvl_s[k - k0]);
-            const uint32_t off = uint32_t(k) * uint32_t(N / 2) + uint32_t((c0 + lane * 16) / 2);
-            const bool in = lane_ok && k < K;
-            M[r] = buf_load_b64(rs_mid, in && lv[r] >= 1 ? off : kSkip);
-            L[r] = buf_load_b64(rs_lo, in && lv[r] >= 2 ? off : kSkip);
-        }
+        for (int b = 0; b < B; ++b) {
+            const float xf = xs[b][lr];
 #pragma unroll
-        for (int r = 0; r < kWStep; ++r) {
-            const uint32_t fill = fill_for_level(lv[r]);
-            uint32_t pa[4], pb[4];
-            assemble8_fill(H[r].x, H[r].y, M[r].x, L[r].x, fill, pa);   // columns 0..7 of the lane
-            assemble8_fill(H[r].z, H[r].w, M[r].y, L[r].y, fill, pb);   // columns 8..15
-            const float v[16] = {lo_half(pa[0]), lo_half(pa[1]), hi_half(pa[0]), hi_half(pa[1]),
-                                 lo_half(pa[2]), lo_half(pa[3]), hi_half(pa[2]), hi_half(pa[3]),
-                                 lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
-                                 lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
-            const int kr = row_of(s, r) - k0;
-#pragma unroll
-            for (int b = 0; b < B; ++b) {
-                const float xf = xs[b][kr];                          // rows at or past K: 0
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[b][i] = fmaf(xf, v[i], acc[b][i]);
-            }
+            for (int i = 0; i < 16; ++i) acc[b][i] = fmaf(xf, v[i], acc[b][i]);
         }
     }
 
-    // ---- the waves' sums meet in LDS, one activation row at a time; thread -> columns tid and tid + 512
-    const int nslab = a.nslab;
+    // ---- sums: over the 8 row lanes by lane exchange, over the waves in LDS, over the slabs in the workspace
 #pragma unroll
-    for (int b = 0; b < B; ++b) {
-        if (b > 0) __syncthreads();
-        float4* dst = reinterpret_cast<float4*>(&red_s[wave][lane * 16]);
+    for (int b = 0; b < B; ++b)
+        for (int o = 8; o < 64; o <<= 1) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dst[i] = make_float4(acc[b][4 * i], acc[b][4 * i + 1], acc[b][4 * i + 2], acc[b][4 * i + 3]);
-        __syncthreads();
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int col = tid + half * kWThreads;
-            float sum = 0.0f;
-#pragma unroll
-            for (int w = 0; w < kWWaves; ++w) sum += red_s[w][col];
-            if (c0 + col < N) {
-                if (nslab == 1) a.y[size_t(b) * N + c0 + col] = sum;
-                else store_agent(&a.part[(size_t(slab_i) * B + b) * N + c0 + col], sum);
-            }
+            for (int i = 0; i < 16; ++i) acc[b][i] += __shfl_xor(acc[b][i], o);
         }
+    if (r == 0) {
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red_s[wave][b][cl * 16 + i] = acc[b][i];
+    }
+    __syncthreads();
+    const int nslab = a.nslab;
+    const int c_out = strip * kWCols + (tid % kWCols), b_out = tid / kWCols;   // thread -> one (activation row, column)
+    const bool mine = tid < B * kWCols && c_out < N;
+    if (mine) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWWaves; ++w) sum += red_s[w][b_out][tid % kWCols];
+        if (nslab == 1) a.y[size_t(b_out) * N + c_out] = sum;
+        else store_agent(&a.part[(size_t(slab_i) * B + b_out) * N + c_out], sum);
     }
     if (nslab == 1) return;
 
-    // ---- the workgroup that finishes last for this column tile adds the slabs, in slab order
+    // ---- the workgroup that finishes last for this strip adds the slabs, in slab order
     stores_done();
     __syncthreads();
-    if (tid == 0) last_s = take_ticket(&a.count[tile]) == nslab - 1;
+    if (tid == 0) last_s = take_ticket(&a.count[strip]) == nslab - 1;
     __syncthreads();
     if (!last_s) return;
-    for (int idx = tid; idx < B * kWCols; idx += kWThreads) {
-        const int b = idx / kWCols, col = idx % kWCols;
-        if (c0 + col >= N) continue;
+    if (mine) {
         float sum = 0.0f;
         for (int s0 = 0; s0 < nslab; s0 += 8) {   // eight slabs' words in flight; the additions stay in slab order
             float p[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                p[i] = s0 + i < nslab ? load_agent(&a.part[(size_t(s0 + i) * B + b) * N + c0 + col]) : 0.0f;
+                p[i] = s0 + i < nslab ? load_agent(&a.part[(size_t(s0 + i) * B + b_out) * N + c_out]) : 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) sum += p[i];
         }
-        a.y[size_t(b) * N + c0 + col] = sum;
+        a.y[size_t(b_out) * N + c_out] = sum;
     }
-    if (tid == 0) store_agent(&a.count[tile], 0);   // ready for the next call
+    if (tid == 0) store_agent(&a.count[strip], 0);   // ready for the next call
 }
 
 // W [K][N] fp16 -> planes and rowmax: one workgroup per row, a thread packs 16 columns at a time
@@ -272,8 +266,7 @@ bool wshape_ok(int K, int N)
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 size_t part_bytes(int K, int N)
 {
-    // the fewest rows per slab the launcher ever picks gives the most slabs
-    return align256(size_t((K + 63) / 64) * AKW_MAX_B * size_t(N) * sizeof(float));
+    return align256(size_t((K + akv::kWSlab - 1) / akv::kWSlab) * AKW_MAX_B * size_t(N) * sizeof(float));
 }
 size_t count_bytes(int N) { return align256(size_t((N + akv::kWCols - 1) / akv::kWCols) * sizeof(int32_t)); }
 
@@ -346,8 +339,7 @@ akv_status akw_gemv(const akw_weights* w, const uint16_t* x, int32_t B, float* y
         return akv::fail_msg(AKV_EWORKSPACE, "workspace NULL, misaligned or smaller than %zu bytes", need);
     akv::GemvArgs a;
     a.K = w->K; a.N = w->N;
-    a.slab = akv::gemv_slab_rows(w->K, w->N, akv::compute_units());
-    a.nslab = (w->K + a.slab - 1) / a.slab;
+    a.nslab = (w->K + akv::kWSlab - 1) / akv::kWSlab;
     a.hi = w->hi; a.mid = w->mid; a.lo = w->lo; a.rowmax = w->rowmax; a.x = x; a.y = y;
     a.part = static_cast<float*>(workspace);
     a.count = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + part_bytes(w->K, w->N));

@@ -77,7 +77,7 @@ def test_weight_layout_sizes_and_shape_checks(A):
     sz = A.akw_layout_sizes(4096, 11008)
     e = 4096 * 11008
     assert (sz.hi, sz.mid, sz.lo, sz.rowmax) == (e, e // 2, e // 2, 4096 * 2)
-    assert sz.workspace % 256 == 0 and sz.workspace >= (4096 // 64) * 4 * 11008 * 4
+    assert sz.workspace % 256 == 0 and sz.workspace >= (4096 // 512) * 4 * 11008 * 4
     for bad in ((4096, 11000), (4100, 4096), (0, 16), (65536, 32768)):
         with pytest.raises(A.AkvError) as e_:
             A.akw_layout_sizes(*bad)

@@ -236,6 +236,21 @@ def main():
             "deviation_from_fp16_attention": {"max_abs": float(dev16.abs().max()),
                                               "rel_l2": float(dev16.norm() / o16.double().norm())}}
         del kp, vp
+        # ------------------------------------------------------------ the second workload (weight GEMV under Rule 1), briefly
+        torch.cuda.empty_cache()
+        from paper_2409_16546_amd import bench_weights
+        gemv = {}
+        for shape in ("attn_proj", "mlp_up", "mlp_down"):
+            m = bench_weights.measure(shape, 1, steps)
+            gemv[shape] = {"K": m["config"]["K"], "N": m["config"]["N"], "us": m["value"],
+                           "avg_bits_W": m["bytes"]["avg_bits_W"], "GBps": m["roofline"]["achieved"],
+                           "frac_of_peak": m["roofline"]["frac"], "control_group_16bit_us": m["control_group_16bit_us"],
+                           "blas_fp16_matmul_us": m["blas_fp16_matmul_us"]}
+            torch.cuda.empty_cache()
+        log("[bench] weight GEMV (B=1): " + ", ".join(f"{k} {v['us']} us ({v['avg_bits_W']} bits, 16-bit control "
+                                                       f"{v['control_group_16bit_us']} us, BLAS {v['blas_fp16_matmul_us']} us)"
+                                                       for k, v in gemv.items()))
+        result["weight_gemv"] = gemv
 
     if args.pmc_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)

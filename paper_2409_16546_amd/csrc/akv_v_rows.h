@@ -79,8 +79,10 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 // One wave walks token rows of (b, h) in batches of 8*KG rows (KG groups of 8 rows; lane -> row lane/8 of the
 // group and the 16-channel slice lane%8): batch i covers rows t_first + i*batch_stride .. + 8*KG - 1,
 // i < nbatches.  Three stages per batch, software-pipelined over DL + 1 named buffers:
-//   L  issue the HI loads and the logit loads (lane j < 8*KG holds the logit of row j of the batch);
-//   D  softmax weight and score exponent once per row, handed to the 8 lanes of the row by lane permutes;
+//   L  issue the HI loads and the logit load (lane j < 8*KG*G holds the logit of row j / G of the batch for query
+//      head j % G: one load for all heads);
+//   D  softmax weight and score exponent once per (row, head), in that lane, handed to the 8 lanes of the row by lane
+//      permutes;
 //      Rule 2 on the HI bytes; MID / LO loads of the rows that need them (the others are issued out of
 //      range: nothing is fetched);
 //   F  assemble the fp16 values, multiply-adds.
@@ -102,27 +104,32 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
     if (nbatches <= 0) return;
     const int lane = threadIdx.x & 63;
     const int r = lane >> 3, cl = lane & 7;
-    const int jj = lane % RB;                      // row of the batch whose score this lane computes
+    // lane j < RB * G computes the score of row j / G of the batch for query head j % G: every (row, head) pair once
+    static_assert(RB * G <= 64 && (G & (G - 1)) == 0, "one lane per (row of the batch, query head)");
+    const int jrow = lane / G, jg = lane % G;
+    const bool jlane = lane < RB * G;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const size_t bh = size_t(b) * Hkv + h;
 
-    __amdgpu_buffer_rsrc_t rs_lg[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-        rs_lg[g] = make_rsrc(a.logits + (size_t(b) * Hq + size_t(h) * G + g) * Ncap, uint32_t(len) * 4u);
+    // the logits of the G query heads of the group lie Ncap floats apart: one descriptor over all of them
+    const __amdgpu_buffer_rsrc_t rs_lg = make_rsrc(a.logits + (size_t(b) * Hq + size_t(h) * G) * Ncap, uint32_t(G) * uint32_t(Ncap) * 4u);
     const __amdgpu_buffer_rsrc_t rs_hi = make_rsrc(a.v_hi + bh * Ncap * kD, uint32_t(len) * kD);
     const __amdgpu_buffer_rsrc_t rs_mid = make_rsrc(a.v_mid + bh * Ncap * (kD / 2), uint32_t(len) * (kD / 2));
     const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(a.v_lo + bh * Ncap * (kD / 2), uint32_t(len) * (kD / 2));
     const uint32_t voff_hi = uint32_t(r) * kD + uint32_t(cl) * 16;
     const uint32_t voff_nib = uint32_t(r) * (kD / 2) + uint32_t(cl) * 8;
-    const uint32_t voff_lg = uint32_t(jj) * 4;
-    int src[KG];                                   // byte address of lane gr*8 + r for the lane permutes
+    const uint32_t voff_lg = (uint32_t(jg) * uint32_t(Ncap) + uint32_t(jrow)) * 4u;
+    int src[KG];                                   // byte address of the first score lane of row gr*8 + r, for the lane permutes
 #pragma unroll
-    for (int gr = 0; gr < KG; ++gr) src[gr] = (gr * 8 + r) * 4;
+    for (int gr = 0; gr < KG; ++gr) src[gr] = (gr * 8 + r) * G * 4;
+    float Mlane = Mg[0];                           // the global max of this lane's query head
+#pragma unroll
+    for (int g = 1; g < G; ++g) Mlane = jg == g ? Mg[g] : Mlane;
+    float zl = 0.0f;                               // sum of this lane's weights (rows j / G of the batches, head j % G)
 
     struct Batch {
         u32x4_t hi[KG];
-        float lg[G];
+        float lg;
         u32x2_t mid[KG], lo[KG];
         float p[KG][G];
         uint32_t fill[KG];
@@ -134,10 +141,9 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
 #pragma unroll
         for (int gr = 0; gr < KG; ++gr) X.hi[gr] = buf_load_b128(rs_hi, voff_hi + base + gr * 8 * kD);
     };
-    auto Llg = [&](Batch& X, int bt) {
-        const uint32_t base = bt < nbatches ? uint32_t(row0(bt)) * 4u : kSkip;
-#pragma unroll
-        for (int g = 0; g < G; ++g) X.lg[g] = bits_float(buf_load_b32(rs_lg[g], voff_lg + base));
+    auto Llg = [&](Batch& X, int bt) {   // one load for all heads; rows at or past len and idle lanes ask out of range
+        const bool on = bt < nbatches && jlane && row0(bt) + jrow < len;
+        X.lg = bits_float(buf_load_b32(rs_lg, on ? voff_lg + uint32_t(row0(bt)) * 4u : kSkip));
     };
     auto D = [&](Batch& X, int bt) {
         uint32_t offm[KG], offl[KG];
@@ -146,16 +152,13 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
         if (bt < nbatches) {   // uniform; arithmetic only -- the loads below are issued in any case
             const int t0 = row0(bt);
             const int nvalid = min(len - t0, RB);       // rows of the batch inside the sequence (may be <= 0)
-            float pj[G];
-            int ahat = kAMin;
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float x = score_x(X.lg[g], Mg[g], a.c);
-                const int ag = score_a(x);
-                ahat = ag > ahat ? ag : ahat;
-                pj[g] = lane < nvalid ? __builtin_amdgcn_exp2f(x) : 0.0f;
-                z[g] += pj[g];
-            }
+            const float x = score_x(X.lg, Mlane, a.c);
+            int ahat = score_a(x);                      // then the maximum over the G heads of the row (adjacent lanes)
+            const float pj = jlane && jrow < nvalid ? __builtin_amdgcn_exp2f(x) : 0.0f;
+            zl += pj;
+            if (G >= 2) ahat = max(ahat, __builtin_amdgcn_update_dpp(ahat, ahat, 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+            if (G >= 4) ahat = max(ahat, __builtin_amdgcn_update_dpp(ahat, ahat, 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+            if (G >= 8) ahat = max(ahat, __builtin_amdgcn_update_dpp(ahat, ahat, 0x141, 0xF, 0xF, false));   // row_half_mirror
             const uint32_t ssw = __builtin_amdgcn_perm(0u, uint32_t(ahat + 64), 0x00000000u);   // (Ahat + 64) in every byte
             uint32_t Fw;   // bit 7: the row-independent test for level >= 1 holds, bit 15: the one for level 2
             if (vr.force >= 0) Fw = vr.force == 2 ? 0x8080u : (vr.force == 1 ? 0x0080u : 0u);
@@ -166,7 +169,7 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
                 const uint32_t Fg = (uint32_t)__builtin_amdgcn_ds_bpermute(src[gr], (int)Fw);
 #pragma unroll
                 for (int g = 0; g < G; ++g)
-                    X.p[gr][g] = bits_float((uint32_t)__builtin_amdgcn_ds_bpermute(src[gr], (int)float_bits(pj[g])));
+                    X.p[gr][g] = bits_float((uint32_t)__builtin_amdgcn_ds_bpermute(src[gr] + 4 * g, (int)float_bits(pj)));
                 const uint32_t hw[4] = {X.hi[gr].x, X.hi[gr].y, X.hi[gr].z, X.hi[gr].w};
                 uint32_t any1 = Fg, any2 = Fg >> 8;   // bit 15 of Fg implies bit 7: stray bits in any1 do no harm
 #pragma unroll
@@ -262,6 +265,8 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
             F(ring[k], i + k);
         }
     }
+#pragma unroll
+    for (int g = 0; g < G; ++g) z[g] += jg == g ? zl : 0.0f;
 }
 
 // sum acc over the 8 row lanes of a wave (lanes with the same lane % 8) and z over all lanes; afterwards

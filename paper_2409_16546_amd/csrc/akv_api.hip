@@ -212,7 +212,7 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
         // the fixed costs per workgroup (Rule 2 constants, pipeline start, partial results) are paid once per slot
         const int cus = compute_units();
         const int G = a.s.Hq / a.s.Hkv;
-        const int per_cu = G <= 1 ? 4 : (G <= 4 ? 3 : 1);   // resident V workgroups per compute unit (register budget)
+        const int per_cu = G <= 1 ? 4 : (G <= 2 ? 3 : (G <= 4 ? 2 : 1));   // resident V workgroups per compute unit (register budget)
         const long pairs = long(a.s.B) * a.s.Hkv;
         const long per_pair = std::max(1L, long(cus) * per_cu / pairs);
         long chunk = (a.max_len + per_pair - 1) / per_pair;

@@ -1,10 +1,10 @@
 // Decode attention, token-split path: the tokens of every (sequence, KV head) are spread over many
-// workgroups (long contexts, few heads).  Three kernels:
-//   K kernel    Rule 1 levels + q.K~, one 256-token block per wave;
-//   mid kernel  max, score exponents and their histogram per 1024-token slice; the workgroup of a (sequence,
-//               KV head) that finishes last finds the top-k from the histograms and computes O_est and the result
-//               exponents;
-//   V kernel    Rule 2 + S.V~ over 512-token chunks; the workgroup that finishes last combines the chunks.
+// workgroups (long contexts, few heads).  Four kernels:
+//   K kernel          Rule 1 levels + q.K~, one 256-token block per wave;
+//   slice kernel      max, score exponents, their histogram and the local top-k candidates per 1024-token slice;
+//   selection kernel  one workgroup per (sequence, KV head): the top-k from the slices' histograms and candidates,
+//                     O_est and the result exponents;
+//   V kernel          Rule 2 + S.V~ over chunks of tokens; the workgroup that finishes last combines the chunks.
 // Sections "Quantization of K-Cache", "Quantization of V-Cache", "Runtime of AlignedKV".
 #include "akv_common.h"
 #include "akv_k_tile.h"
@@ -24,7 +24,7 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
     const int h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63;
     const int Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
-    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all three kernels
+    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all four kernels
     const int wave_u = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int blk = blockIdx.x * kKWaves + wave_u;
     if (blockIdx.x * kMidSlice >= len) return;   // whole workgroup beyond the sequence (uniform)
@@ -42,53 +42,56 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
     }
 }
 
-// Mid kernel: workgroup = 256 threads = one slice of kMidSlice tokens of one (sequence, KV head).
-// Every workgroup derives the global max logit from the block maxima and, per query head, (1) builds the histogram
-// of score exponents of its slice and leaves it in the workspace as running sums over the buckets, (2) selects the
+// Mid step in two kernels.
+// Slice kernel: workgroup = 256 threads = one slice of kMidSlice tokens of one (sequence, KV head).  Every workgroup
+// derives the global max logit from the block maxima and, per query head (a wave each), (1) builds the histogram of
+// score exponents of its slice and leaves it in the workspace as running sums over the buckets, (2) selects the
 // approximate top-k' of its own slice -- a superset of what the whole sequence can select from it, because the
 // cut bucket of the sequence is never later than the slice's own -- and leaves those candidates (token, bucket,
-// weight, in token order) in the workspace.  Device-scope stores; the producer waits for their acknowledgement
-// and takes a ticket.  The workgroup that draws the last ticket of the pair gives each query head of the group
-// to one of its waves: the wave adds the slices' running sums (the first bucket where the total reaches k' is the
-// cut), reads two words per slice to learn how many selected tokens precede each slice and which slices hold
-// any, and takes the selection out of those slices' candidate lists (lane = candidate, ballots give the order);
-// then all threads compute O_est and the result exponents head by head.  Everything that grows with the length
-// of the sequence is spread over the slices; every dependent step of the last workgroup is one round trip to
-// memory; nobody waits for anybody.
+// weight, in token order) in the workspace.  Little LDS, so that every slice of a long batch is resident at once.
+// Selection kernel: one workgroup per (sequence, KV head); each query head of the group goes to one of its waves:
+// the wave adds the slices' running sums (the first bucket where the total reaches k' is the cut), reads two words
+// per slice to learn how many selected tokens precede each slice and which slices hold any, and takes the
+// selection out of those slices' candidate lists (lane = candidate, ballots give the order); then all threads
+// compute O_est and the result exponents -- the V rows of all query heads are asked for before the first is used.
+// Everything that grows with the length of the sequence is spread over the slices; every dependent step of the
+// selection is one round trip to memory.
 template <int G>
-__global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
+__global__ __launch_bounds__(256, (G <= 4 ? 8 : 4)) void split_slice_kernel(DecodeArgs a)   // every slice of a long batch resident at once
 {
     constexpr int NT = 256, kWaves = NT / 64;
     static_assert(kMidSlice == NT * 4, "a thread owns four tokens of the slice");
-    static_assert(kWaves <= kMidSets, "a selection per wave");
-    __shared__ MidShared ms;
     __shared__ float red_s[G][kWaves];
-    __shared__ int last_s;
-    __shared__ int list_s[kWaves][AKV_MAX_TOPK], list_lt[kWaves][AKV_MAX_TOPK], list_eq[kWaves][AKV_MAX_TOPK];
+    __shared__ float M_s[G];
+    __shared__ int cntw_s[kWaves][kBuckets + 1];
 
     const int slice = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
+    const int Hq = a.s.Hq, Ncap = a.s.Ncap, NB = Ncap / kTB;
     const int S = (Ncap + kMidSlice - 1) / kMidSlice;   // slices per query head in the workspace
-    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all three kernels
-    const size_t bh = size_t(b) * Hkv + h;
+    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all four kernels
     if (slice * kMidSlice >= len) return;   // uniform; also every empty sequence
-    const int nblk = (len + kTB - 1) / kTB, nsl = (len + kMidSlice - 1) / kMidSlice;
+    const int nblk = (len + kTB - 1) / kTB;
     const int kk = a.topk < len ? a.topk : len;
 
-    // M = max over the block maxima (exact, order-free)
+    // M = max over the block maxima (exact, order-free); the loads of all query heads of the group go out together
+    float mg[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) mg[g] = tid < nblk ? a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + tid] : -INFINITY;
+    for (int i = tid + NT; i < nblk; i += NT)
+#pragma unroll
+        for (int g = 0; g < G; ++g) mg[g] = fmaxf(mg[g], a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + i]);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        float m = -INFINITY;
-        for (int i = tid; i < nblk; i += NT) m = fmaxf(m, a.tilemax[(size_t(b) * Hq + size_t(h) * G + g) * NB + i]);
-        m = wave_max(m);
+        const float m = wave_max(mg[g]);
         if (lane == 0) red_s[g][wave] = m;
     }
     __syncthreads();
     if (tid < G) {
         float m = red_s[tid][0];
         for (int w = 1; w < kWaves; ++w) m = fmaxf(m, red_s[tid][w]);
-        ms.M[tid] = m;
+        M_s[tid] = m;
+        if (slice == 0) a.M[size_t(b) * Hq + size_t(h) * G + tid] = m;   // for the kernels that follow
     }
     __syncthreads();
 
@@ -101,11 +104,11 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
         for (int g = wave; g < G; g += kWaves) {
             const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
             const __amdgpu_buffer_rsrc_t rs_lg = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
-            const float M = ms.M[g];
+            const float M = M_s[g];
             u32x4_t w[4];
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) w[q4] = __builtin_amdgcn_raw_buffer_load_b128(rs_lg, uint32_t(t0 + 4 * q4) * 4u, 0, 0);   // past Ncap: zeros
-            int* hw = &ms.cntw[wave][0];
+            int* hw = &cntw_s[wave][0];
             hw[lane] = 0;
             if (lane < 2) hw[64 + lane] = 0;
             float x[16];
@@ -121,13 +124,13 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                 }
             }
             __builtin_amdgcn_wave_barrier();
+            int n64 = 0;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                if (j[i] <= 64) {
-                    atomicAdd(&hw[j[i]], 1);
-                    if (a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[i]);
-                }
+                mid_hist_add(hw, j[i], n64);
+                if (j[i] <= 64 && a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[i]);
             }
+            mid_hist_flush(hw, n64);
             __builtin_amdgcn_wave_barrier();
             const int c = hw[lane];   // bucket `lane` of the slice's histogram
             int J, below;
@@ -136,8 +139,8 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
             {   // running sums over the buckets, for the workgroup that merges the slices
                 const int incl = wave_scan_add(c);
                 int32_t* dst = a.hist + (hq * S + slice) * kHistStride;
-                store_agent(&dst[lane], incl);                      // tokens in buckets 0..lane
-                if (lane == 63) store_agent(&dst[64], in_slice);    // all tokens of the slice
+                dst[lane] = incl;                         // tokens in buckets 0..lane
+                if (lane == 63) dst[64] = in_slice;       // all tokens of the slice
             }
             // the candidates in token order: tokens of each kind in lower lanes from five ballots per kind (one per
             // bit of the lane's count, at most 16)
@@ -161,22 +164,35 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                 if (is_lt || (is_eq && n_eq < fromcut)) {
                     const int pos = n_lt + (n_eq < fromcut ? n_eq : fromcut);
                     const float fl = floorf(x[i]);
-                    store_agent(&a.cand_sel[base + pos], (t0 + i) | (j[i] << 24));
-                    store_agent(&a.cand_phat[base + pos], ldexpf(1.0f + (x[i] - fl), -j[i]));   // as mid_emit
+                    a.cand_sel[base + pos] = (t0 + i) | (j[i] << 24);
+                    a.cand_phat[base + pos] = ldexpf(1.0f + (x[i] - fl), -j[i]);   // as mid_emit
                 }
                 n_lt += is_lt;
                 n_eq += is_eq;
             }
-            if (lane >= kloc) store_agent(&a.cand_sel[base + lane], -1);   // no candidate
+            if (lane >= kloc) a.cand_sel[base + lane] = -1;   // no candidate
         }
     }
-    stores_done();
-    __syncthreads();
-    if (tid == 0) last_s = take_ticket(&a.kcount[bh]) == nsl - 1;
-    __syncthreads();
-    if (!last_s) return;
+}
 
-    // ---- the workgroup that finished last for this (sequence, KV head) ------------------------------------
+template <int G>
+__global__ __launch_bounds__(256) void split_select_kernel(DecodeArgs a)
+{
+    constexpr int NT = 256, kWaves = NT / 64;
+    static_assert(kWaves <= kMidSets, "a selection per wave");
+    __shared__ MidShared ms;
+    __shared__ int list_s[kWaves][AKV_MAX_TOPK], list_lt[kWaves][AKV_MAX_TOPK], list_eq[kWaves][AKV_MAX_TOPK];
+
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
+    const int S = (Ncap + kMidSlice - 1) / kMidSlice;   // slices per query head in the workspace
+    const int len = min(min(a.lens[b], Ncap), a.max_len);
+    const size_t bh = size_t(b) * Hkv + h;
+    if (len <= 0) return;   // uniform: an empty sequence has no selection (the V kernel writes its zeros)
+    const int nsl = (len + kMidSlice - 1) / kMidSlice;
+    const int kk = a.topk < len ? a.topk : len;
+
     int ehat = 32767;   // min over the group of the result exponent of channel tid (tid < D)
     for (int g0 = 0; g0 < G; g0 += kWaves) {
         const int g = g0 + wave;
@@ -188,7 +204,7 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
             for (int s0 = 0; s0 < nsl; s0 += 16) {
                 int v[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) v[i] = s0 + i < nsl ? load_agent(&hist[(s0 + i) * kHistStride + lane]) : 0;
+                for (int i = 0; i < 16; ++i) v[i] = s0 + i < nsl ? hist[(s0 + i) * kHistStride + lane] : 0;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) tot += v[i];
             }
@@ -202,8 +218,8 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                 const int s = s0 + lane;
                 int c_lt = 0, c_le = 0;
                 if (s < nsl) {
-                    if (J > 0) c_lt = load_agent(&hist[s * kHistStride + J - 1]);
-                    c_le = load_agent(&hist[s * kHistStride + J]);
+                    if (J > 0) c_lt = hist[s * kHistStride + J - 1];
+                    c_le = hist[s * kHistStride + J];
                 }
                 const int c_eq = c_le - c_lt;
                 const int i_lt = wave_scan_add(c_lt), i_eq = wave_scan_add(c_eq);   // inclusive over the lanes
@@ -221,14 +237,14 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                 carry_eq += wave_read(i_eq, 63);
             }
             // ---- the selection out of those slices' candidates: lane = candidate (token order inside a slice) ------
-            constexpr int kAhead = 8;   // slices of the list whose candidates are in flight
+            constexpr int kAhead = 16;   // slices of the list whose candidates are in flight
             int cs[kAhead];
             float cp[kAhead];
             auto fetch = [&](int e, int& sel, float& phat) {
                 const bool on = e < nlist;
                 const size_t at = (hq * S + (on ? list_s[wave][e] : 0)) * AKV_MAX_TOPK + lane;
-                sel = on ? load_agent(&a.cand_sel[at]) : -1;
-                phat = on ? load_agent(&a.cand_phat[at]) : 0.0f;
+                sel = on ? a.cand_sel[at] : -1;
+                phat = on ? a.cand_phat[at] : 0.0f;
             };
 #pragma unroll
             for (int k = 0; k < kAhead; ++k) fetch(k, cs[k], cp[k]);
@@ -250,17 +266,21 @@ __global__ __launch_bounds__(256) void split_mid_kernel(DecodeArgs a)
                     fetch(e + k + kAhead, cs[k], cp[k]);
                 }
             }
-            if (lane == 0) a.M[hq] = ms.M[g];
         }
         __syncthreads();
-        for (int w = 0; w < kWaves && g0 + w < G; ++w)   // all threads, head by head (ends with a barrier)
-            mid_oest<NT>(a, bh, size_t(b) * Hq + size_t(h) * G + g0 + w, kk, ms, w, ehat);
+        // all threads: the selected V rows of every head of this round are asked for, then used head by head
+        OestRows<NT> rows[kWaves < G ? kWaves : G];
+#pragma unroll
+        for (int w = 0; w < (kWaves < G ? kWaves : G); ++w)
+            if (g0 + w < G) mid_oest_fetch<NT>(a, bh, kk, ms, w, rows[w]);
+#pragma unroll
+        for (int w = 0; w < (kWaves < G ? kWaves : G); ++w)
+            if (g0 + w < G) mid_oest_finish<NT>(a, size_t(b) * Hq + size_t(h) * G + g0 + w, kk, ms, w, rows[w], ehat);   // ends with a barrier
     }
     if (tid < kD) {
         a.Ehat[bh * kD + tid] = ehat;
         if (a.dbg.Ehat) a.dbg.Ehat[bh * kD + tid] = (int16_t)ehat;
     }
-    if (tid == 0) store_agent(&a.kcount[bh], 0);   // ready for the next call
 }
 
 // Workgroup = kVWaves waves, one (sequence, KV head, kVChunk-token chunk); wave w takes the batches of rows
@@ -275,7 +295,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane >> 3, cl = lane & 7;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
-    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all three kernels
+    const int len = min(min(a.lens[b], Ncap), a.max_len);   // a hint below the true length: the tokens past it are left out, consistently in all four kernels
     const int vchunk = a.vchunk;   // tokens per workgroup: a multiple of kVChunk chosen at launch
     const int c0 = split * vchunk;
     const size_t bh = size_t(b) * Hkv + h;
@@ -301,7 +321,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     }
     // 16 rows per batch, HI bytes fetched four batches ahead: the accumulators of a group of query heads leave room
     // for few waves per SIMD, so each wave keeps more bytes in flight
-    constexpr int KG = G >= 4 ? 1 : 2, RB = 8 * KG, DL = G == 2 ? 4 : 3;
+    constexpr int KG = G >= 8 ? 1 : 2, RB = 8 * KG, DL = G == 2 ? 4 : 3;
     const u32x4_t none[1][KG] = {};
     v_rows<G, KG, DEBUG, 0, DL>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
     v_reduce_rows<G>(acc, z);
@@ -362,7 +382,9 @@ static hipError_t launch_split_g(const DecodeArgs& a, hipStream_t st, hipEvent_t
     const dim3 kgrid((a.max_len + tile - 1) / tile, a.s.Hkv, a.s.B), kblock(64 * kKWaves);
     hipLaunchKernelGGL((split_k_kernel<G>), kgrid, kblock, 0, st, a);
     if (hipError_t e = hipGetLastError()) return e;
-    hipLaunchKernelGGL((split_mid_kernel<G>), kgrid, dim3(256), 0, st, a);   // one workgroup per slice here as well
+    hipLaunchKernelGGL((split_slice_kernel<G>), kgrid, dim3(256), 0, st, a);   // one workgroup per slice here as well
+    if (hipError_t e = hipGetLastError()) return e;
+    hipLaunchKernelGGL((split_select_kernel<G>), dim3(a.s.Hkv, a.s.B), dim3(256), 0, st, a);
     if (hipError_t e = hipGetLastError()) return e;
     if (mid_event)
         if (hipError_t e = hipEventRecord(mid_event, st)) return e;

@@ -33,6 +33,21 @@ __device__ __forceinline__ void mid_emit(MidShared& sm, int set, int pos, int t,
     sm.phat[set][pos] = ldexpf(1.0f + f, -j);   // 2^x with a linear mantissa, the exponent floored at -64
 }
 
+// One token per lane into a histogram in LDS (buckets 0..64; a token that does not count has j > 64; called by all
+// lanes of a wave).  The floor bucket 64 takes every weight below 2^-64 -- most tokens of a peaked softmax -- and an
+// LDS atomic whose lanes all hit one address costs a cycle per lane of the one LDS unit the waves of a compute unit
+// share: that bucket is counted with a ballot (n64, wave-uniform, handed to mid_hist_flush at the end), only the
+// others with atomics.
+__device__ __forceinline__ void mid_hist_add(int* hist, int j, int& n64)
+{
+    n64 += __builtin_popcountll(__ballot(j == 64));
+    if (j < 64) atomicAdd(&hist[j], 1);
+}
+__device__ __forceinline__ void mid_hist_flush(int* hist, int n64)
+{
+    if ((threadIdx.x & 63) == 0 && n64 > 0) atomicAdd(&hist[64], n64);
+}
+
 // The cut from bucket totals (lane l of a full wave holds the total of bucket l; bucket 64 can only be the cut if
 // none before it is): first bucket J where the running count reaches kk, and the number of tokens in buckets below it.
 __device__ __forceinline__ void mid_find_cut(int c, int kk, int& J, int& below)
@@ -67,9 +82,10 @@ __device__ __forceinline__ int mid_select_chunk(MidShared& sm, int set, const fl
 {
     constexpr int kWaves = NT / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int n64 = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (j[i] <= 64) atomicAdd(&sm.cntw[wave][j[i]], 1);
+    for (int i = 0; i < 4; ++i) mid_hist_add(&sm.cntw[wave][0], j[i], n64);
+    mid_hist_flush(&sm.cntw[wave][0], n64);
     __syncthreads();
     int tot = 0, before = 0;   // bucket `lane`: all waves / the waves before this one
 #pragma unroll
@@ -108,30 +124,55 @@ __device__ __forceinline__ int mid_select_chunk(MidShared& sm, int set, const fl
 // contains barriers, the last one after the LDS rows have been read): the selected V rows at full 16 bits go to LDS (8 threads per row, all rows in flight together, so
 // that this costs one memory latency), then each channel runs its ordered FMA chain from operands fetched 16 rows
 // at a time.  ehat (thread d < 128: channel d) is lowered to the exponent of the result.
+// The selected V rows of one query head, 16 bits of every element, as they come from memory: thread -> (row
+// tid / 8 + p * NT / 8 of the selection, 16-channel slice tid % 8)
 template <int NT>
-__device__ __forceinline__ void mid_oest(const DecodeArgs& a, size_t bh, size_t hq, int kk, MidShared& sm, int set, int& ehat)
+struct OestRows {
+    static constexpr int kPasses = (AKV_MAX_TOPK + NT / 8 - 1) / (NT / 8);
+    uint4 hi[kPasses];
+    uint2 mid[kPasses], lo[kPasses];
+};
+// issue the loads of the rows sm.sel[set][0 .. kk-1] (nothing waits for them here: a caller with several query
+// heads asks for all of them before it uses the first)
+template <int NT>
+__device__ __forceinline__ void mid_oest_fetch(const DecodeArgs& a, size_t bh, int kk, const MidShared& sm, int set, OestRows<NT>& R)
 {
-    const int tid = threadIdx.x;
-    const int Ncap = a.s.Ncap;
-    for (int row = tid >> 3; row < kk; row += NT / 8) {
-        const int cl = tid & 7;
-        const size_t vrow = bh * Ncap + sm.sel[set][row];
-        const uint4 hi = *reinterpret_cast<const uint4*>(a.v_hi + vrow * kD + cl * 16);
-        const uint2 mid = *reinterpret_cast<const uint2*>(a.v_mid + vrow * (kD / 2) + cl * 8);
-        const uint2 lo = *reinterpret_cast<const uint2*>(a.v_lo + vrow * (kD / 2) + cl * 8);
-        uint32_t pa[4], pb[4];
-        assemble8(hi.x, hi.y, mid.x, lo.x, pa);
-        assemble8(hi.z, hi.w, mid.y, lo.y, pb);
-        uint16_t* dst = reinterpret_cast<uint16_t*>(&sm.v2[row >> 1][cl * 16]) + (row & 1);   // element stride: 2 halves
-        const uint32_t pp[8] = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], pb[2], pb[3]};
+    const int tid = threadIdx.x, cl = tid & 7;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {   // pairs (0,2),(1,3) then (4,6),(5,7) of each eight
-            const uint32_t e = pp[2 * q4], o = pp[2 * q4 + 1];
-            const int base = (q4 >> 1) * 8 + (q4 & 1) * 4;
-            dst[2 * (base + 0)] = (uint16_t)e;
-            dst[2 * (base + 1)] = (uint16_t)o;
-            dst[2 * (base + 2)] = (uint16_t)(e >> 16);
-            dst[2 * (base + 3)] = (uint16_t)(o >> 16);
+    for (int p = 0; p < OestRows<NT>::kPasses; ++p) {
+        const int row = (tid >> 3) + p * (NT / 8);
+        if (row < kk) {
+            const size_t vrow = bh * a.s.Ncap + sm.sel[set][row];
+            R.hi[p] = *reinterpret_cast<const uint4*>(a.v_hi + vrow * kD + cl * 16);
+            R.mid[p] = *reinterpret_cast<const uint2*>(a.v_mid + vrow * (kD / 2) + cl * 8);
+            R.lo[p] = *reinterpret_cast<const uint2*>(a.v_lo + vrow * (kD / 2) + cl * 8);
+        }
+    }
+}
+// rows -> LDS (two rows per word), then each channel runs its ordered FMA chain; ends with a barrier
+template <int NT>
+__device__ __forceinline__ void mid_oest_finish(const DecodeArgs& a, size_t hq, int kk, MidShared& sm, int set, const OestRows<NT>& R,
+                                                int& ehat)
+{
+    const int tid = threadIdx.x, cl = tid & 7;
+#pragma unroll
+    for (int p = 0; p < OestRows<NT>::kPasses; ++p) {
+        const int row = (tid >> 3) + p * (NT / 8);
+        if (row < kk) {
+            uint32_t pa[4], pb[4];
+            assemble8(R.hi[p].x, R.hi[p].y, R.mid[p].x, R.lo[p].x, pa);
+            assemble8(R.hi[p].z, R.hi[p].w, R.mid[p].y, R.lo[p].y, pb);
+            uint16_t* dst = reinterpret_cast<uint16_t*>(&sm.v2[row >> 1][cl * 16]) + (row & 1);   // element stride: 2 halves
+            const uint32_t pp[8] = {pa[0], pa[1], pa[2], pa[3], pb[0], pb[1], pb[2], pb[3]};
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {   // pairs (0,2),(1,3) then (4,6),(5,7) of each eight
+                const uint32_t e = pp[2 * q4], o = pp[2 * q4 + 1];
+                const int base = (q4 >> 1) * 8 + (q4 & 1) * 4;
+                dst[2 * (base + 0)] = (uint16_t)e;
+                dst[2 * (base + 1)] = (uint16_t)o;
+                dst[2 * (base + 2)] = (uint16_t)(e >> 16);
+                dst[2 * (base + 3)] = (uint16_t)(o >> 16);
+            }
         }
     }
     __syncthreads();
@@ -160,6 +201,13 @@ __device__ __forceinline__ void mid_oest(const DecodeArgs& a, size_t bh, size_t 
     }
     if (a.dbg.sel && tid < a.topk) a.dbg.sel[hq * a.topk + tid] = tid < kk ? sm.sel[set][tid] : -1;
     __syncthreads();
+}
+template <int NT>
+__device__ __forceinline__ void mid_oest(const DecodeArgs& a, size_t bh, size_t hq, int kk, MidShared& sm, int set, int& ehat)
+{
+    OestRows<NT> R;
+    mid_oest_fetch<NT>(a, bh, kk, sm, set, R);
+    mid_oest_finish<NT>(a, hq, kk, sm, set, R, ehat);
 }
 
 // Run by one workgroup of NT threads for one (sequence b, KV head h) of len tokens, after every logit of the pair is
@@ -245,18 +293,19 @@ __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int 
             // ---- histogram of score exponents over all chunks -----------------------------------------
             if (tid < kBuckets) cnt_s[tid] = 0;
             __syncthreads();
-            for (int t0 = tid * 4; t0 < len; t0 += kChunk) {
+            int n64 = 0;
+            for (int c0 = 0; c0 < len; c0 += kChunk) {   // uniform trip count: the ballots below need whole waves
+                const int t0 = c0 + tid * 4;
                 float x[4];
-                int j[4];
-                load_score4(t0, x, j);
+                int j[4] = {1000, 1000, 1000, 1000};
+                if (t0 < len) load_score4(t0, x, j);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    if (j[i] <= 64) {
-                        atomicAdd(&cnt_s[j[i]], 1);
-                        if (a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[i]);
-                    }
+                    mid_hist_add(cnt_s, j[i], n64);
+                    if (j[i] <= 64 && a.dbg.a) a.dbg.a[hq * Ncap + t0 + i] = (int8_t)(-j[i]);
                 }
             }
+            mid_hist_flush(cnt_s, n64);
             __syncthreads();
             int J, below;
             mid_find_cut(cnt_s[lane], kk, J, below);

@@ -120,12 +120,12 @@ typedef struct akv_params {
                              kernels then attend to the first max_len tokens only                   */
     const akv_debug *dbg; /* host pointer to a struct of device pointers, or NULL                    */
     void *const *events;  /* host pointer to 3 hipEvent_t, or NULL: the library records them on the
-                             stream before its first kernel, between the K kernel and the V kernel of
+                             stream before its first kernel, in front of the V kernel of
                              the token-split path (on the head-per-workgroup path, which is one kernel:
                              right after event 0) and after its last kernel, so that a caller can time
                              the kernels in place                                                   */
     int32_t path;         /* 0: choose; 1: head-per-workgroup path (one kernel; needs Hq/Hkv <= 4);
-                             2: token-split path (two kernels).  Both give the same decisions.       */
+                             2: token-split path (four kernels).  Both give the same decisions.       */
 } akv_params;
 
 #define AKV_MAX_TOPK 64

@@ -159,20 +159,15 @@ using akv::compute_units;
 
 // Head-per-workgroup or token-split kernels, when the caller leaves the choice to the library.  One head kernel
 // workgroup occupies a compute unit, so `pairs` (sequence, KV head) pairs run in ceil(pairs / CUs) rounds of equal
-// length: the path pays when those rounds are (nearly) full, or when the sequences are so short that the single
-// launch outweighs idle units.  The thresholds are where the two paths crossed when timed over pairs = 64..1024,
-// lengths 1024..16384 and group sizes 1, 2, 4 on MI355X.
+// length: the path pays when there is one round and it is nearly full, or when the sequences are so short that the
+// single launch outweighs idle units.  The thresholds are where the two paths crossed when timed over pairs =
+// 64..1024, lengths 1024..16384 and group sizes 1, 2, 4 on MI355X.
 bool head_path_pays(long pairs, int G, int max_len)
 {
-    if (max_len > 16384) return false;
     const long cus = compute_units();
-    const long rounds = (pairs + cus - 1) / cus;
-    const double fill = double(pairs) / double(rounds * cus);
-    if (rounds == 1) {
-        if (pairs >= 64 && max_len <= (G == 1 ? 2048 : 1024)) return true;
-        return fill >= (G == 4 ? 0.9 : 0.72);
-    }
-    return G == 1 && fill >= 0.9 && max_len >= 2048;
+    if (pairs > cus || pairs < 64) return false;
+    if (max_len <= (G == 1 ? 2048 : 1024)) return true;
+    return max_len <= 8192 && double(pairs) / double(cus) >= (G == 2 ? 0.9 : 0.72);
 }
 
 akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, void* out,

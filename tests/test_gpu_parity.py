@@ -380,12 +380,13 @@ def test_cfg2_full_size_sampled_against_oracle(T):
         say(f"  b={b} h={h}: max-abs {err:.2e} rel-L2 {rl2:.2e}")
 
 
-@pytest.mark.parametrize("cfg", [3, 4, 5])
-def test_full_size_configs_3_to_5_sampled_against_oracle(T, cfg):
-    """Benchmark configurations 3-5 at full size with the library's choice of path: config 3 (B16, MHA, 8192 tokens; the
-    last token is appended inside the step) runs the head-per-workgroup kernel with two blocks per wave and two
-    chunks in the mid step; configs 4 and 5 (GQA 32/8, 32768 tokens / ragged lengths up to 131072) run the
-    token-split kernels.  Three sampled (sequence, KV head) pairs are recomputed by the oracle."""
+@pytest.mark.parametrize("cfg,path", [(3, 0), (3, 1), (4, 0), (5, 0)], ids=["cfg3", "cfg3-head-path", "cfg4", "cfg5"])
+def test_full_size_configs_3_to_5_sampled_against_oracle(T, cfg, path):
+    """Benchmark configurations 3-5 at full size.  With the library's choice of path all three run the token-split
+    kernels (config 3: B16, MHA, 8192 tokens, the last token appended inside the step -- two rounds of pairs;
+    configs 4 and 5: GQA 32/8, 32768 tokens / ragged lengths up to 131072).  Config 3 is also run on the
+    head-per-workgroup kernel (fused append, two blocks per wave, two chunks in the mid step).  Three sampled
+    (sequence, KV head) pairs are recomputed by the oracle."""
     from paper_2409_16546_amd import workloads, binding as A
     from oracle import akv_oracle as O
     w = workloads.make(cfg)
@@ -400,12 +401,12 @@ def test_full_size_configs_3_to_5_sampled_against_oracle(T, cfg):
         kn = torch.stack([w.k[b, :, lens[b] - 1:lens[b]] for b in range(w.B)]).contiguous()
         vn = torch.stack([w.v[b, :, lens[b] - 1:lens[b]] for b in range(w.B)]).contiguous()
         dbg = A.DebugBuffers.allocate(gc)
-        out = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), q, max_len=max(lens), dbg=dbg)
+        out = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), q, max_len=max(lens), dbg=dbg, path=path)
     else:
         gc = T.gpu_cache(w.k, w.v, lens, w.Hq, N)
         dbg = A.DebugBuffers.allocate(gc)
-        out = A.akv_decode_attention(gc, q, max_len=max(lens), dbg=dbg)
-    plain = A.akv_decode_attention(gc, q, max_len=max(lens))           # the launch without exports
+        out = A.akv_decode_attention(gc, q, max_len=max(lens), dbg=dbg, path=path)
+    plain = A.akv_decode_attention(gc, q, max_len=max(lens), path=path)           # the launch without exports
     torch.cuda.synchronize()
     assert torch.equal(plain, out)
     assert gc.lens.cpu().tolist() == lens

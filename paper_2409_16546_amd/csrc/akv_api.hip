@@ -161,11 +161,11 @@ using akv::compute_units;
 // workgroup occupies a compute unit, so `pairs` (sequence, KV head) pairs run in ceil(pairs / CUs) rounds of equal
 // length: the path pays when there is one round and it is nearly full, or when the sequences are so short that the
 // single launch outweighs idle units.  The thresholds are where the two paths crossed when timed over pairs =
-// 64..1024, lengths 1024..16384 and group sizes 1, 2, 4 on MI355X.
+// 32..1024, lengths 1024..16384 and group sizes 1, 2, 4 on MI355X.
 bool head_path_pays(long pairs, int G, int max_len)
 {
     const long cus = compute_units();
-    if (pairs > cus || pairs < 64) return false;
+    if (pairs > cus) return false;
     if (max_len <= (G == 1 ? 2048 : 1024)) return true;
     return max_len <= 8192 && double(pairs) / double(cus) >= (G == 2 ? 0.9 : 0.72);
 }

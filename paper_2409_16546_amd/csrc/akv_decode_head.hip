@@ -60,9 +60,11 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     uint32_t old_m = 0, old_l = 0;   // the nibble bytes the new token shares with its neighbour
     if (appended && tid < kD) {
         k_new_bits = k_new_raw;
-        const size_t nib = k_nibble_index(bh, Ncap, len_old, tid);
-        old_m = a.k_mid[nib];   // in flight together with the loads of the level computation
-        old_l = a.k_lo[nib];
+        if (len_old & 1) {   // an even place opens its nibble byte (never written: zero), an odd one shares it with the token before
+            const size_t nib = k_nibble_index(bh, Ncap, len_old, tid);
+            old_m = a.k_mid[nib];   // in flight together with the loads of the level computation
+            old_l = a.k_lo[nib];
+        }
     }
     const int len = len_old + (appended ? 1 : 0);
     if (len == 0) {                                     // an empty sequence attends to nothing: zeros

@@ -210,6 +210,18 @@ __device__ __forceinline__ u32x4_t buf_load_b128(__amdgpu_buffer_rsrc_t r, uint3
     return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
 }
 
+// The same with the non-temporal hint: cache bytes that are read once per step stream through L2 without pushing out
+// what is read again (the logits between the passes, the lines an appended token is stored into).
+constexpr int kAuxNt = 2;
+__device__ __forceinline__ u32x2_t buf_load_b64_nt(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, kAuxNt);
+}
+__device__ __forceinline__ u32x4_t buf_load_b128_nt(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kAuxNt);
+}
+
 // Data handed from one workgroup to another INSIDE a kernel (logits and tile maxima to the workgroup that
 // runs the mid step, split partials to the one that combines them).  The L2 caches of the eight XCDs are not
 // coherent with each other, and a device-scope fence writes back / invalidates a whole L2, which costs far

@@ -85,7 +85,12 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     const u32x4_t zero4 = {0u, 0u, 0u, 0u};
     u32x4_t kpre[6] = {zero4, zero4, zero4, zero4, zero4, zero4};
     const bool pre_any = blk < blk_end;
-    if (pre_any) k_tile_pre(a, b, h, blk, kpre);
+    // the block the new token goes into is read without the non-temporal hint: its lines stay in L2 for the stores
+    const int keep_blk = appended ? len_old / kTB : -1;
+    if (pre_any) {
+        if (blk == keep_blk) k_tile_pre<false>(a, b, h, blk, kpre);
+        else k_tile_pre<true>(a, b, h, blk, kpre);
+    }
     const uint32_t colmax_used = k_levels_finish<G>(a, b, h, ks, true, k_new_bits, lin);
     float wm[G];
 #pragma unroll
@@ -104,13 +109,15 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     uint8_t* stage = &kstage[wave_u][0];
     if (pre_any) {   // the block whose first HI bytes are already in flight
         float tm[G];
-        k_tile<G>(a, b, h, blk, len_old, ks, 0, tm, kpre, true, own, stage);
+        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_old, ks, 0, tm, kpre, true, own, stage);
+        else k_tile<G, true>(a, b, h, blk, len_old, ks, 0, tm, kpre, true, own, stage);
         blk += 1;
         fold(tm);
     }
     while (blk < blk_end) {
         float tm[G], later[G][4];
-        k_tile<G>(a, b, h, blk, len_old, ks, 0, tm, kpre, false, later, stage);
+        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_old, ks, 0, tm, kpre, false, later, stage);
+        else k_tile<G, true>(a, b, h, blk, len_old, ks, 0, tm, kpre, false, later, stage);
         blk += 1;
         fold(tm);
     }

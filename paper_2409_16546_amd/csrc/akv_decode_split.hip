@@ -323,7 +323,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     // for few waves per SIMD, so each wave keeps more bytes in flight
     constexpr int KG = G >= 8 ? 1 : 2, RB = 8 * KG, DL = G == 2 ? 4 : 3;
     const u32x4_t none[1][KG] = {};
-    v_rows<G, KG, DEBUG, 0, DL>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
+    v_rows<G, KG, DEBUG, 0, DL, true>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll

@@ -148,21 +148,25 @@ constexpr int kKStage = 4096;     // bytes of LDS staging per wave
 
 // HI bytes of the first three groups of a tile, issued before the levels are known (they are always read):
 // pre[] is handed to k_tile (use_pre = true) for the same block.
+template <bool NT = true>
 __device__ __forceinline__ void k_tile_pre(const DecodeArgs& a, int b, int h, int blk, u32x4_t (&pre)[6])
 {
     const int lane = threadIdx.x & 63;
     const size_t bh = size_t(b) * a.s.Hkv + h;
     const __amdgpu_buffer_rsrc_t rh = make_rsrc(a.k_hi + (bh * a.s.Ncap + size_t(blk) * kTB) * kD, uint32_t(kTB) * kD);
 #pragma unroll
-    for (int i = 0; i < 6; ++i) pre[i] = buf_load_b128(rh, uint32_t(lane) * 16 + i * 1024);
+    for (int i = 0; i < 6; ++i) pre[i] = NT ? buf_load_b128_nt(rh, uint32_t(lane) * 16 + i * 1024) : buf_load_b128(rh, uint32_t(lane) * 16 + i * 1024);
 }
 
-template <int G>
+// NT: the block's bytes are read with the non-temporal hint (they are read once per step); a caller that is about to
+// store into the block's lines (fused append) reads that one block without it, so that the lines stay in L2.
+template <int G, bool NT = true>
 __device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int blk, int len, const KShared<G>& ks,
                                        int aux, float (&tile_max)[G], const u32x4_t (&pre)[6], bool use_pre,
                                        float (&acc)[G][4], uint8_t* stage)
 {
     constexpr int U = kKU;
+    constexpr int kAux = NT ? kAuxNt : 0;
     const int lane = threadIdx.x & 63;
     const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const size_t bh = size_t(b) * Hkv + h;
@@ -193,16 +197,16 @@ __device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int bl
     // groups past the last column are issued through descriptors of size zero: nothing is fetched
     auto issue_hi = [&](Group& gr, int d0) {
         const __amdgpu_buffer_rsrc_t rh = make_rsrc(hi_blk, d0 < kD ? uint32_t(kTB) * kD : 0u);
-        gr.h0 = __builtin_amdgcn_raw_buffer_load_b128(rh, voff, d0 * kTB, 0);
-        gr.h1 = __builtin_amdgcn_raw_buffer_load_b128(rh, voff + 1024, d0 * kTB, 0);
+        gr.h0 = __builtin_amdgcn_raw_buffer_load_b128(rh, voff, d0 * kTB, kAux);
+        gr.h1 = __builtin_amdgcn_raw_buffer_load_b128(rh, voff + 1024, d0 * kTB, kAux);
     };
     auto issue_nib = [&](Group& gr, int d0) {
         const uint32_t bm = bits_at(nm0, nm1, d0), bl = bits_at(nl0, nl1, d0);
         const uint32_t size = d0 < kD ? uint32_t(kTB) * (kD / 2) : 0u;
         const __amdgpu_buffer_rsrc_t rm = make_rsrc(mid_blk, size), rl = make_rsrc(lo_blk, size);
         const uint32_t base = voff + uint32_t(d0 < kD ? d0 : 0) * (kTB / 2);
-        gr.m = __builtin_amdgcn_raw_buffer_load_b128(rm, ((bm >> col) & 1u) ? base : kSkip, 0, 0);
-        gr.l = __builtin_amdgcn_raw_buffer_load_b128(rl, ((bl >> col) & 1u) ? base : kSkip, 0, 0);
+        gr.m = __builtin_amdgcn_raw_buffer_load_b128(rm, ((bm >> col) & 1u) ? base : kSkip, 0, kAux);
+        gr.l = __builtin_amdgcn_raw_buffer_load_b128(rl, ((bl >> col) & 1u) ? base : kSkip, 0, kAux);
     };
     auto issue = [&](Group& gr, int d0) {
         issue_hi(gr, d0);

@@ -92,7 +92,9 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 // is forced to zero.  acc accumulates sum_t p_t * v~_td per lane (to be reduced over the 8 row lanes, then
 // over waves, by the caller); z accumulates sum_t p_t per lane (to be summed over all 64 lanes).
 // NPRE > 0: pre holds the HI bytes of batches 0 .. NPRE-1 (v_prefetch_hi) if pre_ok.
-template <int G, int KG, bool DEBUG, int NPRE, int DL = 2>
+// NT: the V bytes are read with the non-temporal hint (measured: it pays in the token-split V kernel, where the logits
+// and the chunk partials of other workgroups share the caches, and costs in the head-per-workgroup kernel).
+template <int G, int KG, bool DEBUG, int NPRE, int DL = 2, bool NT = false>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
                                        int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
                                        float (&z)[G], const u32x4_t (&pre)[NPRE > 0 ? NPRE : 1][KG], bool pre_ok)
@@ -139,7 +141,7 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
     auto Lhi = [&](Batch& X, int bt) {
         const uint32_t base = bt < nbatches ? uint32_t(row0(bt)) * kD : kSkip;
 #pragma unroll
-        for (int gr = 0; gr < KG; ++gr) X.hi[gr] = buf_load_b128(rs_hi, voff_hi + base + gr * 8 * kD);
+        for (int gr = 0; gr < KG; ++gr) X.hi[gr] = NT ? buf_load_b128_nt(rs_hi, voff_hi + base + gr * 8 * kD) : buf_load_b128(rs_hi, voff_hi + base + gr * 8 * kD);
     };
     auto Llg = [&](Batch& X, int bt) {   // one load for all heads; rows at or past len and idle lanes ask out of range
         const bool on = bt < nbatches && jlane && row0(bt) + jrow < len;
@@ -216,8 +218,8 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
         }
 #pragma unroll
         for (int gr = 0; gr < KG; ++gr) {
-            X.mid[gr] = buf_load_b64(rs_mid, offm[gr]);
-            X.lo[gr] = buf_load_b64(rs_lo, offl[gr]);
+            X.mid[gr] = NT ? buf_load_b64_nt(rs_mid, offm[gr]) : buf_load_b64(rs_mid, offm[gr]);
+            X.lo[gr] = NT ? buf_load_b64_nt(rs_lo, offl[gr]) : buf_load_b64(rs_lo, offl[gr]);
         }
     };
     auto F = [&](const Batch& X, int bt) {

@@ -38,7 +38,7 @@ def measure(cfg: int, steps: int = 50, dev: str = "cuda:0") -> dict:
     w = workloads.make(cfg)
     N, G = w.Ncap, w.Hq // w.Hkv
     fp16_cache_bytes = 2 * w.B * w.Hkv * N * w.D * 2
-    R = max(1, min(8, -(-(768 << 20) // fp16_cache_bytes)))      # copies, so that the rotating footprint passes 768 MB
+    R = max(1, min(64, -(-(768 << 20) // fp16_cache_bytes)))     # copies, so that the rotating footprint passes 768 MB
     kd, vd, qd, lens = w.k.to(dev), w.v.to(dev), w.q.to(dev), w.lens.to(dev)
     caches = []
     for _ in range(R):

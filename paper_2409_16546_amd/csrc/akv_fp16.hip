@@ -3,9 +3,18 @@
 // Same streaming design as the plane kernels (16-byte coalesced loads straight into registers, wave
 // shuffles for the reductions, token-axis splits combined at the end), but K and V of a chunk are read in
 // one kernel with a chunk-local softmax (split-KV), since nothing has to be decided between the passes.
+#include <type_traits>
+
 #include "akv_common.h"
 
 namespace akv {
+
+// 16 bytes with the non-temporal hint (the token-split kernels stream K and V once per step, as the aligned ones do)
+__device__ __forceinline__ uint4 load16_nt(const uint16_t* p)
+{
+    const u32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(w.x, w.y, w.z, w.w);
+}
 
 constexpr int kFChunk = 512;   // tokens per workgroup
 constexpr int kFWaves = 4;
@@ -69,7 +78,7 @@ __global__ __launch_bounds__(64 * kFWaves) void fp16_kernel(F16Args a)
         const int tl = it * (4 * kFWaves) + wave * 4 + r, t = c0 + tl;
         const bool valid = t < len;
         uint4 w = make_uint4(0, 0, 0, 0);
-        if (valid) w = *reinterpret_cast<const uint4*>(a.k + (bh * Ncap + t) * kD + cl * 8);
+        if (valid) w = load16_nt(a.k + (bh * Ncap + t) * kD + cl * 8);
         float kf[8];
         unpack8h(w, kf);
 #pragma unroll
@@ -107,7 +116,7 @@ __global__ __launch_bounds__(64 * kFWaves) void fp16_kernel(F16Args a)
         const int tl = it * (4 * kFWaves) + wave * 4 + r, t = c0 + tl;
         const bool valid = t < len;
         uint4 w = make_uint4(0, 0, 0, 0);
-        if (valid) w = *reinterpret_cast<const uint4*>(a.v + (bh * Ncap + t) * kD + cl * 8);
+        if (valid) w = load16_nt(a.v + (bh * Ncap + t) * kD + cl * 8);
         float vf[8];
         unpack8h(w, vf);
 #pragma unroll
@@ -204,23 +213,27 @@ __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restr
         unpack8h(w, qf[g]);
     }
     const int nbatch = (len + 31) / 32;
-    auto load_batch = [&](const __amdgpu_buffer_rsrc_t& rs, int bt, u32x4_t (&w)[kLoads]) {
+    // the same cache hints as the aligned kernels of this shape: K non-temporal, V not
+    auto load_batch = [&](const __amdgpu_buffer_rsrc_t& rs, int bt, u32x4_t (&w)[kLoads], auto nt) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int t = bt * 32 + j * 4 + r;
-            w[j] = buf_load_b128(rs, (bt < nbatch && t < len) ? uint32_t(t) * (kD * 2) + cl * 16 : kSkip);
+            const uint32_t off = (bt < nbatch && t < len) ? uint32_t(t) * (kD * 2) + cl * 16 : kSkip;
+            w[j] = decltype(nt)::value ? buf_load_b128_nt(rs, off) : buf_load_b128(rs, off);
         }
     };
+    constexpr std::true_type kNt{};
+    constexpr std::false_type kKeep{};
 
     // ---- phase 1: logits and their maximum ---------------------------------------------------------
     float mloc[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) mloc[g] = -INFINITY;
     u32x4_t wc[kLoads], wn[kLoads];
-    load_batch(rs_k, wave, wc);
+    load_batch(rs_k, wave, wc, kNt);
 #pragma unroll 1
     for (int bt = wave; bt < nbatch; bt += kWaves) {
-        load_batch(rs_k, bt + kWaves, wn);
+        load_batch(rs_k, bt + kWaves, wn, kNt);
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int t = bt * 32 + j * 4 + r;
@@ -262,10 +275,10 @@ __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restr
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[g][i] = 0.0f;
     }
-    load_batch(rs_v, wave, wc);
+    load_batch(rs_v, wave, wc, kKeep);
 #pragma unroll 1
     for (int bt = wave; bt < nbatch; bt += kWaves) {
-        load_batch(rs_v, bt + kWaves, wn);
+        load_batch(rs_v, bt + kWaves, wn, kKeep);
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int t = bt * 32 + j * 4 + r;

@@ -240,19 +240,23 @@ hipError_t launch_zero(void* p, size_t bytes, hipStream_t st)
     return hipGetLastError();
 }
 
-// Plain streaming read (16 bytes per lane, four loads in flight per lane, grid-stride): the read ceiling of the
+// Plain streaming read (16 bytes per lane with the non-temporal hint, four loads in flight per lane, grid-stride): the read ceiling of the
 // device that the roofline fractions of the other kernels are put beside.
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* sink)
 {
+    auto ld = [](const uint4* q) {   // non-temporal, as the decode kernels read the bytes they stream
+        const u32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(q));
+        return make_uint4(w.x, w.y, w.z, w.w);
+    };
     const size_t stride = size_t(gridDim.x) * 256;
     size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
     uint32_t acc = 0;
     for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        const uint4 a = ld(p + i), b = ld(p + i + stride), c = ld(p + i + 2 * stride), d = ld(p + i + 3 * stride);
         acc += a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
     for (; i < n16; i += stride) {
-        const uint4 a = p[i];
+        const uint4 a = ld(p + i);
         acc += a.x ^ a.y ^ a.z ^ a.w;
     }
     if (acc == 0x9E3779B9u) *sink = acc;   // keeps the loads alive; practically never taken

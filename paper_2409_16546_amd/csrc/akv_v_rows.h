@@ -92,8 +92,9 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 // is forced to zero.  acc accumulates sum_t p_t * v~_td per lane (to be reduced over the 8 row lanes, then
 // over waves, by the caller); z accumulates sum_t p_t per lane (to be summed over all 64 lanes).
 // NPRE > 0: pre holds the HI bytes of batches 0 .. NPRE-1 (v_prefetch_hi) if pre_ok.
-// NT: the V bytes are read with the non-temporal hint (measured: it pays in the token-split V kernel, where the logits
-// and the chunk partials of other workgroups share the caches, and costs in the head-per-workgroup kernel).
+// NT: the HI bytes are read with the non-temporal hint (measured: it pays in the token-split V kernel, where the logits
+// and the chunk partials of other workgroups share the caches, and costs in the head-per-workgroup kernel); the MID
+// and LO bytes always are (it pays in both).
 template <int G, int KG, bool DEBUG, int NPRE, int DL = 2, bool NT = false>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
                                        int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
@@ -218,8 +219,8 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
         }
 #pragma unroll
         for (int gr = 0; gr < KG; ++gr) {
-            X.mid[gr] = NT ? buf_load_b64_nt(rs_mid, offm[gr]) : buf_load_b64(rs_mid, offm[gr]);
-            X.lo[gr] = NT ? buf_load_b64_nt(rs_lo, offl[gr]) : buf_load_b64(rs_lo, offl[gr]);
+            X.mid[gr] = buf_load_b64_nt(rs_mid, offm[gr]);
+            X.lo[gr] = buf_load_b64_nt(rs_lo, offl[gr]);
         }
     };
     auto F = [&](const Batch& X, int bt) {

@@ -18,7 +18,7 @@ constexpr int kMaxG = 8;           // query heads per KV head supported
 
 // K pass: one wave covers one 256-token block (4 consecutive tokens per lane).
 constexpr int kKWaves = 4;                         // waves per workgroup
-constexpr int kMidSlice = kTB * kKWaves;           // tokens per workgroup of the K kernel and of the mid kernel
+constexpr int kMidSlice = kTB * kKWaves;           // tokens per workgroup of the K kernel and of the slice kernel
 constexpr int kHistStride = 66;                    // ints per slice histogram in the workspace (65 buckets)
 // V pass: one workgroup covers kVChunk tokens; a wave reads 8 token rows per step.
 constexpr int kVWaves = 4;
@@ -86,7 +86,7 @@ struct DecodeArgs {
     int32_t* hist;       // per-slice histograms of the token-split path
     int32_t* cand_sel;   // per-slice candidates of the token-split path
     float* cand_phat;
-    int32_t* kcount;     // [B][Hkv] arrival counters (zero on entry, zero on exit)
+    int32_t* kcount;     // [B][Hkv] spare control words (kept zero; the selection runs in a kernel of its own)
     int32_t* vcount;
     akv_debug dbg;       // device pointers or NULL
 };
@@ -222,8 +222,8 @@ __device__ __forceinline__ u32x4_t buf_load_b128_nt(__amdgpu_buffer_rsrc_t r, ui
     return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kAuxNt);
 }
 
-// Data handed from one workgroup to another INSIDE a kernel (logits and tile maxima to the workgroup that
-// runs the mid step, split partials to the one that combines them).  The L2 caches of the eight XCDs are not
+// Data handed from one workgroup to another INSIDE a kernel (the chunk partials of the V kernel and the slab
+// partials of the weight GEMV, to the workgroup that combines them).  The L2 caches of the eight XCDs are not
 // coherent with each other, and a device-scope fence writes back / invalidates a whole L2, which costs far
 // more than the data is worth.  So these few words are moved with device-scope relaxed accesses (sc1: written
 // through to memory, read from memory), the producer waits for its stores to be acknowledged before it takes

@@ -4,9 +4,8 @@ reading all 16 bits); bytes read by plane from the exported decisions; effective
 
 Run on the GPU:  python -m paper_2409_16546_amd.bench_configs [--configs 1 3 4 5] [--steps 50]
 ``bench.py`` at the repository root is the benchmark of record (configuration 2, one appended token per step,
-rotating cache copies); this module is the survey over the other shapes.  Configurations 1 and 2 are small enough
-to sit in the memory-side cache when a single copy is stepped repeatedly, so their caches are rotated here as well;
-3..5 exceed every cache by themselves.
+rotating cache copies); this module is the survey over the other shapes.  The calls rotate over as many cache copies as it takes to pass 2 GB (a single copy of a small configuration would sit
+in the 256-MB memory-side cache, and two copies of configuration 2 still hit it in part).
 """
 from __future__ import annotations
 
@@ -38,7 +37,7 @@ def measure(cfg: int, steps: int = 50, dev: str = "cuda:0") -> dict:
     w = workloads.make(cfg)
     N, G = w.Ncap, w.Hq // w.Hkv
     fp16_cache_bytes = 2 * w.B * w.Hkv * N * w.D * 2
-    R = max(1, min(64, -(-(768 << 20) // fp16_cache_bytes)))     # copies, so that the rotating footprint passes 768 MB
+    R = max(1, min(64, -(-(2 << 30) // fp16_cache_bytes)))       # copies, so that the rotating footprint passes 2 GB, eight times the memory-side cache
     kd, vd, qd, lens = w.k.to(dev), w.v.to(dev), w.q.to(dev), w.lens.to(dev)
     caches = []
     for _ in range(R):

@@ -132,6 +132,43 @@ def test_decode_matches_oracle(T, name, cfg, over, lens, params, path):
         f"V rows {r.counts[3:6] // 128}")
 
 
+def test_decode_random_shapes_lengths_and_parameters(T):
+    """Seeded sweep over what the targeted cases fix by hand: group size, head and batch counts, capacity, ragged lengths
+    (empty, one token, block and chunk edges, full), guard bits, top-k, scale, both paths, adaptive and append-then-decode."""
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    rng = np.random.default_rng(20240916)
+    edges = [0, 1, 2, 15, 16, 17, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025]
+    for case in range(24):
+        G = int(rng.choice([1, 1, 2, 4, 8]))
+        Hkv, B = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        Ncap = int(rng.choice([256, 512, 1024, 1280, 2304]))
+        lens = [int(rng.choice(edges)) if rng.random() < 0.5 else int(rng.integers(0, Ncap + 1)) for _ in range(B)]
+        lens = [min(n, Ncap) for n in lens]
+        params = dict(guard_bits=int(rng.integers(0, 3)), topk=int(rng.choice([1, 5, 32, 64])))
+        if rng.random() < 0.3:
+            params["scale"] = float(rng.choice([0.02, 0.3]))
+        path = 2 if G > 4 else int(rng.integers(1, 3))
+        cfg = int(rng.choice([1, 2, 3, 4]))
+        w = workloads.make(cfg, B=B, Hq=Hkv * G, Hkv=Hkv, N=max(max(lens), 1), seed=1000 + case)
+        say(f"random case {case}: cfg{cfg} G{G} Hkv{Hkv} B{B} Ncap{Ncap} lens{lens} {params} path{path}")
+        gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, Ncap=Ncap, path=path, **params)
+        T.assert_cache_equal(gc, oc)
+        T.assert_decode_equal(out, dbg, r, lens, G, f"random case {case}")
+        # one more token where there is room, appended and attended to in one call
+        room = [n < Ncap for n in lens]
+        if any(room):
+            gen = torch.Generator().manual_seed(case)
+            kn = torch.randn(B, Hkv, 1, 128, generator=gen).half()
+            vn = torch.randn(B, Hkv, 1, 128, generator=gen).half()
+            O.append(oc, T.bits(kn), T.bits(vn), np.array([1] * B, np.int32))          # full sequences are refused on both sides
+            out2 = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), w.q.to(DEV), dbg=dbg, path=path, **params)
+            torch.cuda.synchronize()
+            r2 = O.decode_attention(oc, T.bits(w.q), **params)
+            T.assert_cache_equal(gc, oc)
+            T.assert_decode_equal(out2, dbg, r2, oc.lens.tolist(), G, f"random case {case} + 1 token")
+
+
 def test_decode_edge_lengths_empty_one_and_smallest_capacity(T):
     from paper_2409_16546_amd import workloads
     say("decode parity: lens 0 / 1 / 255 / 256, Ncap 256")

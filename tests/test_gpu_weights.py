@@ -93,6 +93,21 @@ def test_gemv_matches_oracle(T, name, shape, B, kw):
     say(f"  levels {np.bincount(r.lvl, minlength=3).tolist()}  max err / S_n {rel:.2e}")
 
 
+def test_gemv_random_shapes_and_parameters(T):
+    """Seeded sweep over shapes (ragged strips and slabs, a single strip, a single slab), batch and guard bits."""
+    from paper_2409_16546_amd import workloads
+    rng = np.random.default_rng(424242)
+    for case in range(16):
+        K = int(rng.choice([8, 64, 504, 512, 520, 1000, 1536, 2056]))
+        N = int(rng.choice([16, 112, 128, 144, 1024, 2064, 4112]))
+        B = int(rng.integers(1, 5))
+        kw = dict(guard_bits=int(rng.integers(0, 4)))
+        say(f"gemv random case {case}: K{K} N{N} B{B} {kw}")
+        wl = workloads.make_weights((K, N), B, outliers=int(rng.integers(0, 5)), seed=3000 + case)
+        _, _, y, lvl, r = both(T, wl, **kw)
+        check(y, lvl, r, f"random case {case}")
+
+
 def test_gemv_zero_rows_subnormals_and_zero_activations(T):
     from paper_2409_16546_amd import workloads
     say("gemv: zero / subnormal rows, zero activations")

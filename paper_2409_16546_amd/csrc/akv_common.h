@@ -258,11 +258,18 @@ __device__ __forceinline__ int take_ticket(int32_t* counter)
 
 // Variant of assemble8 taking the fill for unread bits as a per-byte constant OR-ed into the low bytes:
 // level 0 -> 0x80808080 (with M = L = 0), level 1 -> 0x08080808 (with L = 0), level 2 -> 0.
+// (a & mask) | (b & ~mask) in one instruction (the compiler settles for two ANDs and a three-way OR otherwise)
+__device__ __forceinline__ uint32_t bit_select(uint32_t mask, uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "s"(mask), "v"(a), "v"(b));
+    return r;
+}
 __device__ __forceinline__ void assemble8_fill(uint32_t H0, uint32_t H1, uint32_t M, uint32_t L, uint32_t fill,
                                                uint32_t (&p)[4])
 {
-    const uint32_t ev = ((M << 4) & 0xF0F0F0F0u) | (L & 0x0F0F0F0Fu) | fill;
-    const uint32_t od = (M & 0xF0F0F0F0u) | ((L >> 4) & 0x0F0F0F0Fu) | fill;
+    const uint32_t ev = bit_select(0xF0F0F0F0u, M << 4, L) | fill;
+    const uint32_t od = bit_select(0xF0F0F0F0u, M, L >> 4) | fill;
     p[0] = __builtin_amdgcn_perm(H0, ev, 0x06010400u);
     p[1] = __builtin_amdgcn_perm(H0, od, 0x07010500u);
     p[2] = __builtin_amdgcn_perm(H1, ev, 0x06030402u);

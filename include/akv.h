@@ -86,6 +86,8 @@ typedef struct akv_sizes {
  *   flags [AKV_NFLAGS + B] int32 sticky device-side status words, then one arrival counter per sequence
  *                                used inside akv_append (zero between calls)
  * Slots that were never written hold zero after akv_cache_reset.
+ * Alignment: the planes and colmax 16 bytes, lens and flags 4 bytes; every other device array an entry point takes
+ * (q, out, k_new, v_new, k, v, k_out, v_out) 16 bytes.  A misaligned pointer is refused with AKV_EINVAL.
  */
 typedef struct akv_cache {
     akv_shape shape;

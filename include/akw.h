@@ -18,7 +18,8 @@
  *
  * Conventions: those of akv.h (device pointers owned by the caller unless named "host", nothing is
  * allocated or synchronised, work is enqueued on the caller's stream, akv_status / akv_last_error()).
- * Shapes: K % 8 == 0, K <= 2^20, N % 16 == 0, K * N < 2^31, 1 <= B <= AKW_MAX_B.  x, rowmax: 16-byte aligned.
+ * Shapes: K % 8 == 0, K <= 2^20, N % 16 == 0, K * N < 2^31, 1 <= B <= AKW_MAX_B.
+ * Every device array (planes, rowmax, W, x, y) is 16-byte aligned; a misaligned one is refused with AKV_EINVAL.
  */
 #ifndef AKW_H
 #define AKW_H

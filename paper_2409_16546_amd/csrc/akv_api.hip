@@ -12,14 +12,9 @@ namespace {
 
 thread_local char g_err[256] = "";
 
-akv_status fail(akv_status st, const char* fmt, ...)
-{
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(g_err, sizeof g_err, fmt, ap);
-    va_end(ap);
-    return st;
-}
+constexpr auto fail = &akv::fail_msg;   // one error record for every entry point of the library
+
+bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
 bool shape_ok(const akv_shape& s)
 {
@@ -36,6 +31,9 @@ akv_status check_cache(const akv_cache* c)
                     c->shape.B, c->shape.Hq, c->shape.Hkv, c->shape.D, c->shape.Ncap);
     if (!c->k_hi || !c->k_mid || !c->k_lo || !c->v_hi || !c->v_mid || !c->v_lo || !c->colmax || !c->lens || !c->flags)
         return fail(AKV_EINVAL, "cache has a NULL plane / colmax / lens / flags pointer");
+    if (!aligned16(c->k_hi) || !aligned16(c->k_mid) || !aligned16(c->k_lo) || !aligned16(c->v_hi) || !aligned16(c->v_mid) ||
+        !aligned16(c->v_lo) || !aligned16(c->colmax) || reinterpret_cast<uintptr_t>(c->lens) % 4 || reinterpret_cast<uintptr_t>(c->flags) % 4)
+        return fail(AKV_EINVAL, "cache planes and colmax must be 16-byte aligned, lens and flags 4-byte aligned");
     return AKV_OK;
 }
 
@@ -47,7 +45,6 @@ akv_status hip_fail(hipError_t e, const char* what)
 }  // namespace
 
 namespace akv {
-// the same error record for the other entry points of the library
 akv_status fail_msg(akv_status st, const char* fmt, ...)
 {
     va_list ap;
@@ -102,7 +99,6 @@ akv_status akv_cache_reset(const akv_cache* cache, void* stream)
         {cache->v_mid, sz.v_mid}, {cache->v_lo, sz.v_lo}, {cache->colmax, sz.colmax}, {cache->lens, sz.lens},
         {cache->flags, sz.flags}};
     for (auto& bf : bufs) {
-        if (reinterpret_cast<uintptr_t>(bf.p) % 16) return fail(AKV_EINVAL, "cache buffers must be 16-byte aligned");
         if (hipError_t e = akv::launch_zero(bf.p, bf.n, s)) return hip_fail(e, "zero launch");
     }
     return AKV_OK;
@@ -127,6 +123,7 @@ akv_status akv_append(const akv_cache* cache, const uint16_t* k_new, const uint1
     if (akv_status st = check_cache(cache)) return st;
     if (n < 0 || n > cache->shape.Ncap) return fail(AKV_EINVAL, "n = %d out of range 0..Ncap", n);
     if (n > 0 && (!k_new || !v_new)) return fail(AKV_EINVAL, "k_new / v_new is NULL");
+    if (!aligned16(k_new) || !aligned16(v_new)) return fail(AKV_EINVAL, "k_new / v_new must be 16-byte aligned");
     if (hipError_t e = akv::launch_append(*cache, k_new, v_new, n_new, n, static_cast<hipStream_t>(stream)))
         return hip_fail(e, "append launch");
     return AKV_OK;
@@ -145,6 +142,7 @@ akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, 
 {
     if (akv_status st = check_cache(cache)) return st;
     if (!k_out && !v_out) return AKV_OK;
+    if (!aligned16(k_out) || !aligned16(v_out)) return fail(AKV_EINVAL, "k_out / v_out must be 16-byte aligned");
     if (hipError_t e = akv::launch_unpack(*cache, k_out, v_out, static_cast<hipStream_t>(stream)))
         return hip_fail(e, "unpack launch");
     return AKV_OK;
@@ -154,7 +152,6 @@ akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, 
 
 namespace {
 
-// decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])
 using akv::compute_units;
 
 // Head-per-workgroup or token-split kernels, when the caller leaves the choice to the library.  One head kernel
@@ -170,11 +167,14 @@ bool head_path_pays(long pairs, int G, int max_len)
     return max_len <= 8192 && double(pairs) / double(cus) >= (G == 2 ? 0.9 : 0.72);
 }
 
+// decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])
 akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, void* out,
                        const akv_params* params, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (akv_status st = check_cache(cache)) return st;
     if (!q || !out) return fail(AKV_EINVAL, "q / out is NULL");
+    if (!aligned16(q) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new))
+        return fail(AKV_EINVAL, "q, out, k_new and v_new must be 16-byte aligned");
     akv_params p;
     std::memset(&p, 0, sizeof p);
     p.force_level = -1;
@@ -279,6 +279,7 @@ akv_status akv_fp16_decode_attention(const akv_shape* shape, const uint16_t* k, 
 {
     if (!shape || !shape_ok(*shape)) return fail(AKV_EINVAL, "bad shape");
     if (!k || !v || !lens || !q || !out) return fail(AKV_EINVAL, "NULL pointer argument");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(q) || !aligned16(out)) return fail(AKV_EINVAL, "k, v, q and out must be 16-byte aligned");
     if (out_dtype != 0 && out_dtype != 1) return fail(AKV_EINVAL, "out_dtype = %d is neither 0 (f32) nor 1 (f16)", out_dtype);
     if (max_len < 0 || max_len > shape->Ncap) return fail(AKV_EINVAL, "max_len = %d out of range 0..Ncap", max_len);
     const size_t need = akv::fp16_workspace_bytes(*shape);

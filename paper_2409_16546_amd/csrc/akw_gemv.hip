@@ -264,6 +264,7 @@ bool wshape_ok(int K, int N)
     return K >= 8 && K % 8 == 0 && K <= (1 << 20) && N >= 16 && N % 16 == 0 && (long long)K * N < (1LL << 31);
 }
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 size_t part_bytes(int K, int N)
 {
     return align256(size_t((K + akv::kWSlab - 1) / akv::kWSlab) * AKW_MAX_B * size_t(N) * sizeof(float));
@@ -276,6 +277,8 @@ akv_status check_weights(const akw_weights* w)
     if (!wshape_ok(w->K, w->N))
         return akv::fail_msg(AKV_EINVAL, "bad shape: K=%d N=%d (need K %% 8 == 0, K <= 2^20, N %% 16 == 0, K*N < 2^31)", w->K, w->N);
     if (!w->hi || !w->mid || !w->lo || !w->rowmax) return akv::fail_msg(AKV_EINVAL, "weights has a NULL plane / rowmax pointer");
+    if (!aligned16(w->hi) || !aligned16(w->mid) || !aligned16(w->lo) || !aligned16(w->rowmax))
+        return akv::fail_msg(AKV_EINVAL, "the planes and rowmax must be 16-byte aligned");
     return AKV_OK;
 }
 
@@ -307,7 +310,7 @@ akv_status akw_workspace_init(int32_t K, int32_t N, void* workspace, size_t work
 akv_status akw_pack(const akw_weights* w, const uint16_t* W, void* stream)
 {
     if (akv_status st = check_weights(w)) return st;
-    if (!W) return akv::fail_msg(AKV_EINVAL, "W is NULL");
+    if (!W || !aligned16(W)) return akv::fail_msg(AKV_EINVAL, "W is NULL or not 16-byte aligned");
     hipLaunchKernelGGL(akv::pack_kernel, dim3(w->K), dim3(256), 0, static_cast<hipStream_t>(stream), w->K, w->N, W, w->hi, w->mid,
                        w->lo, w->rowmax);
     if (hipError_t e = hipGetLastError()) return akv::fail_msg(AKV_EHIP, "pack launch: %s", hipGetErrorString(e));
@@ -317,7 +320,7 @@ akv_status akw_pack(const akw_weights* w, const uint16_t* W, void* stream)
 akv_status akw_unpack(const akw_weights* w, uint16_t* W_out, void* stream)
 {
     if (akv_status st = check_weights(w)) return st;
-    if (!W_out) return akv::fail_msg(AKV_EINVAL, "W_out is NULL");
+    if (!W_out || !aligned16(W_out)) return akv::fail_msg(AKV_EINVAL, "W_out is NULL or not 16-byte aligned");
     hipLaunchKernelGGL(akv::unpack_kernel, dim3(w->K), dim3(256), 0, static_cast<hipStream_t>(stream), w->K, w->N, w->hi, w->mid,
                        w->lo, W_out);
     if (hipError_t e = hipGetLastError()) return akv::fail_msg(AKV_EHIP, "unpack launch: %s", hipGetErrorString(e));
@@ -329,6 +332,7 @@ akv_status akw_gemv(const akw_weights* w, const uint16_t* x, int32_t B, float* y
 {
     if (akv_status st = check_weights(w)) return st;
     if (!x || !y) return akv::fail_msg(AKV_EINVAL, "x / y is NULL");
+    if (!aligned16(x) || !aligned16(y)) return akv::fail_msg(AKV_EINVAL, "x and y must be 16-byte aligned");
     if (B < 1 || B > AKW_MAX_B) return akv::fail_msg(AKV_EINVAL, "B = %d out of range 1..%d", B, AKW_MAX_B);
     akw_params p = {0, -1, nullptr};
     if (params) p = *params;

@@ -82,3 +82,41 @@ def test_weight_layout_sizes_and_shape_checks(A):
         with pytest.raises(A.AkvError) as e_:
             A.akw_layout_sizes(*bad)
         assert e_.value.status == A.AKV_EINVAL and "bad shape" in str(e_.value)
+
+
+def test_misaligned_pointers_are_refused_before_anything_is_launched(A):
+    # the addresses are made up: every call below is turned away by the host-side checks, which come first
+    L = A.lib()
+    planes = {n: 0x10000 * (i + 1) for i, n in enumerate(("k_hi", "k_mid", "k_lo", "v_hi", "v_mid", "v_lo", "colmax",
+                                                           "lens", "flags"))}
+    shape = A.akv_shape(1, 4, 4, 128, 256)
+    good = A.akv_cache(shape, **planes)
+    q, out, ws = 0x200000, 0x300000, 0x400000
+
+    def refused(st, word):
+        assert st == A.AKV_EINVAL and word in L.akv_last_error().decode()
+
+    refused(L.akv_decode_attention(C.byref(good), q + 2, out, None, ws, 1 << 30, None), "aligned")
+    refused(L.akv_decode_attention(C.byref(good), q, out + 4, None, ws, 1 << 30, None), "aligned")
+    refused(L.akv_append_decode_attention(C.byref(good), q + 8, q, q, out, None, ws, 1 << 30, None), "aligned")
+    for name in ("k_hi", "v_lo", "colmax"):
+        bad = A.akv_cache(shape, **{**planes, name: planes[name] + 8})
+        refused(L.akv_decode_attention(C.byref(bad), q, out, None, ws, 1 << 30, None), "aligned")
+    bad = A.akv_cache(shape, **{**planes, "lens": planes["lens"] + 2})
+    refused(L.akv_append(C.byref(bad), q, q, None, 1, None), "aligned")
+    refused(L.akv_append(C.byref(good), q + 2, q, None, 1, None), "aligned")
+    refused(L.akv_unpack(C.byref(good), q + 2, None, None), "aligned")
+    refused(L.akv_fp16_decode_attention(C.byref(shape), q, q + 6, q, q, out, 0.0, 0, 0, ws, 1 << 30, None), "aligned")
+    assert L.akv_decode_attention(C.byref(good), q, out, None, ws + 16, 1 << 30, None) == A.AKV_EWORKSPACE
+
+
+def test_misaligned_weight_arrays_are_refused(A):
+    L = A.lib()
+    w = A.akw_weights(64, 32, 0x10000, 0x20000, 0x30000, 0x40000)
+    x, y, ws = 0x50000, 0x60000, 0x70000
+    assert L.akw_gemv(C.byref(w), x + 2, 1, y, None, ws, 1 << 30, None) == A.AKV_EINVAL
+    assert L.akw_gemv(C.byref(w), x, 1, y + 4, None, ws, 1 << 30, None) == A.AKV_EINVAL
+    assert L.akw_pack(C.byref(w), x + 2, None) == A.AKV_EINVAL
+    assert L.akw_unpack(C.byref(A.akw_weights(64, 32, 0x10008, 0x20000, 0x30000, 0x40000)), x, None) == A.AKV_EINVAL
+    assert "aligned" in L.akv_last_error().decode()
+    assert L.akw_gemv(C.byref(w), x, 1, y, None, ws + 8, 1 << 30, None) == A.AKV_EWORKSPACE

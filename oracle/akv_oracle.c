@@ -503,3 +503,13 @@ int akvo_max_threads(void)
     return 1;
 #endif
 }
+
+/* number of threads the parallel loops over (sequence, head) use from now on (timing at one thread and at all) */
+void akvo_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

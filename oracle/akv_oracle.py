@@ -57,6 +57,8 @@ def lib():
         _lib.akvo_fp16_attention.restype = C.c_int
         _lib.akvo_fp16_attention.argtypes = [C.c_int] * 5 + [C.c_void_p] * 4 + [C.c_float, C.c_void_p]
         _lib.akvo_max_threads.restype = C.c_int
+        _lib.akvo_set_threads.restype = None
+        _lib.akvo_set_threads.argtypes = [C.c_int]
     return _lib
 
 
@@ -178,3 +180,8 @@ def fp16_attention(k: np.ndarray, v: np.ndarray, lens: np.ndarray, q: np.ndarray
 
 def max_threads() -> int:
     return lib().akvo_max_threads()
+
+
+def set_threads(n: int) -> None:
+    """Threads used by the loops over (sequence, head) from now on."""
+    lib().akvo_set_threads(int(n))

@@ -35,7 +35,7 @@ struct WsLayout {
     size_t Ehat;     // int32 [B][Hkv][D]
     size_t partO;    // float [B][Hq][v_splits(Ncap)][D]
     size_t partZ;    // float [B][Hq][v_splits(Ncap)]
-    size_t control;  // int32 [2][B][Hkv]: arrival counters of the K pass and of the V pass (zero between calls)
+    size_t control;  // int32 [2][B][Hkv]: a spare word and the arrival counter of the V kernel per (sequence, KV head); zero between calls
     size_t control_bytes;
     size_t total;
 };
@@ -91,7 +91,6 @@ struct DecodeArgs {
     akv_debug dbg;       // device pointers or NULL
 };
 
-// host launchers (defined next to their kernels)
 // Store one token of one (sequence, KV head) at position t: thread d (0..127) owns K channel d and is the
 // only writer of that column's nibble bytes; threads 0..63 own the V nibble byte of channels 2d, 2d+1.
 // Returns |k| as bits (for K_colmax).  "Dynamic Quantization": all 16 bits are kept, in three planes.
@@ -138,6 +137,7 @@ __device__ __forceinline__ uint32_t store_token(uint8_t* k_hi, uint8_t* k_mid, u
 }
 #endif
 
+// host side: the error record, the device's size, and the launchers (each defined next to its kernels)
 akv_status fail_msg(akv_status st, const char* fmt, ...);   // records the text akv_last_error() returns
 int compute_units();                                         // of the current device (256 on MI355X), looked up once
 hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16_t* v_new, const int32_t* n_new, int n,
@@ -145,7 +145,7 @@ hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t* sink, hipStream_t st);
 hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, hipStream_t st);
-hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event);   // K kernel, V kernel
+hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event);   // four kernels; mid_event (may be null) is recorded in front of the last
 hipError_t launch_decode_head(const DecodeArgs& a, hipStream_t st);                         // one kernel, a head per workgroup
 bool head_path_supported(const akv_shape& s);
 hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v, const int32_t* lens, const uint16_t* q,
@@ -329,11 +329,6 @@ __device__ __forceinline__ float wave_max(float v)
 #pragma unroll
     for (int k = 0; k < 6; ++k) v = step(v, k);
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-__device__ __forceinline__ int wave_sum_int(int v)
-{
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
 }
 
 #endif  // __HIPCC__

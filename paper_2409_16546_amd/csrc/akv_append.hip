@@ -248,14 +248,17 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
         const u32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(q));
         return make_uint4(w.x, w.y, w.z, w.w);
     };
-    const size_t stride = size_t(gridDim.x) * 256;
-    size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+    // every XCD reads one contiguous eighth of the buffer (workgroup L runs on XCD L % 8), as the decode kernels do
+    const size_t region = (n16 + kXcds - 1) / kXcds, first = (blockIdx.x % kXcds) * region;
+    const size_t end = first + region < n16 ? first + region : n16;
+    const size_t stride = size_t(gridDim.x / kXcds) * 256;
+    size_t i = first + size_t(blockIdx.x / kXcds) * 256 + threadIdx.x;
     uint32_t acc = 0;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
+    for (; i + 3 * stride < end; i += 4 * stride) {
         const uint4 a = ld(p + i), b = ld(p + i + stride), c = ld(p + i + 2 * stride), d = ld(p + i + 3 * stride);
         acc += a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
-    for (; i < n16; i += stride) {
+    for (; i < end; i += stride) {
         const uint4 a = ld(p + i);
         acc += a.x ^ a.y ^ a.z ^ a.w;
     }
@@ -268,7 +271,7 @@ hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t* sink, hipSt
     if (n16 == 0) return hipSuccess;
     size_t blocks = (n16 + 1023) / 1024;
     blocks = blocks < 1 ? 1 : (blocks > 8192 ? 8192 : blocks);
-    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<const uint4*>(p), n16, sink);
+    hipLaunchKernelGGL(stream_read_kernel, dim3(xcd_grid(blocks)), dim3(256), 0, st, reinterpret_cast<const uint4*>(p), n16, sink);
     return hipGetLastError();
 }
 

@@ -152,8 +152,17 @@ hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v,
                        void* out, float scale, int out_dtype, int max_len, void* ws, hipStream_t st);
 size_t fp16_workspace_bytes(const akv_shape& s);
 
+// Workgroups of a launch are dealt to the eight XCDs in turn: workgroup L of a one-dimensional grid runs on XCD
+// L % 8.  The streaming kernels give every XCD one contiguous eighth of the work instead of every eighth item, so
+// that the bytes an XCD reads form one stretch of each plane (its address translations and its L2 cover an eighth
+// of the pages instead of all of them): the grid is padded to a multiple of eight workgroups, workgroup L takes
+// item xcd_work_index(L, grid) and leaves at once when that is not below the number of items.
+constexpr int kXcds = 8;
+inline unsigned xcd_grid(size_t items) { return (unsigned)((items + kXcds - 1) / kXcds * kXcds); }
+
 // ------------------------------------------------------------------ device helpers
 #if defined(__HIPCC__)
+__device__ __forceinline__ int xcd_work_index(int L, int nwg) { return (L % kXcds) * (nwg / kXcds) + L / kXcds; }
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 

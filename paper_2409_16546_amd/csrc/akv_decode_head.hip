@@ -38,10 +38,12 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     __shared__ float red_s[kWaves][G][kD + 1];
     __shared__ __align__(16) uint8_t kstage[kWaves][kKStage];
 
-    const int h = blockIdx.x, b = blockIdx.y;
+    const int Hq = a.s.Hq, Hkv = a.s.Hkv, Ncap = a.s.Ncap;
+    const int pair = xcd_work_index(blockIdx.x, gridDim.x);   // an XCD takes consecutive heads
+    if (pair >= a.s.B * Hkv) return;
+    const int h = pair % Hkv, b = pair / Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane >> 3, cl = lane & 7;
-    const int Hq = a.s.Hq, Hkv = a.s.Hkv, Ncap = a.s.Ncap;
     const size_t bh = size_t(b) * Hkv + h;
     int ticket = -1;
     // q and K_colmax of the head are asked for first: everything below queues up behind them
@@ -209,7 +211,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
 template <int G, int NT>
 static hipError_t launch_head_g(const DecodeArgs& a, hipStream_t st)
 {
-    const dim3 grid(a.s.Hkv, a.s.B), block(NT);
+    const dim3 grid(xcd_grid(size_t(a.s.B) * a.s.Hkv)), block(NT);
     if (a.dbg.needV || a.dbg.appliedV) hipLaunchKernelGGL((head_kernel<G, NT, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((head_kernel<G, NT, false>), grid, block, 0, st, a);
     return hipGetLastError();

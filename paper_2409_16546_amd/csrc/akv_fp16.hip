@@ -187,10 +187,12 @@ __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restr
     __shared__ float max_s[kWaves][G];
     __shared__ float red_s[kWaves][G][kD + 1];
 
-    const int h = blockIdx.x, b = blockIdx.y;
+    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
+    const int pair = xcd_work_index(blockIdx.x, gridDim.x);   // an XCD takes consecutive heads
+    if (pair >= a.s.B * Hkv) return;
+    const int h = pair % Hkv, b = pair / Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane >> 4, cl = lane & 15;
-    const int Hkv = a.s.Hkv, Hq = a.s.Hq, Ncap = a.s.Ncap;
     const int len = min(min(a.lens[b], Ncap), a.max_len);
     if (len == 0) {
         for (int idx = tid; idx < G * kD; idx += NT) {
@@ -344,7 +346,7 @@ hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v,
     float* logits = reinterpret_cast<float*>(p);
     const int G = s.Hq / s.Hkv;
     if (G <= 2 && s.B * s.Hkv >= 192 && max_len <= 16384) {   // enough heads to fill the chip: one workgroup per head
-        const dim3 hgrid(s.Hkv, s.B);
+        const dim3 hgrid(xcd_grid(size_t(s.B) * s.Hkv));
         if (G == 1) hipLaunchKernelGGL((fp16_head_kernel<1, 1024>), hgrid, dim3(1024), 0, st, a, logits);
         else hipLaunchKernelGGL((fp16_head_kernel<2, 1024>), hgrid, dim3(1024), 0, st, a, logits);
         return hipGetLastError();

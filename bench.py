@@ -238,7 +238,7 @@ def main():
         result["streaming_read_ceiling"] = {
             "GBps": round(stream_gbps, 1), "frac_of_peak": round(stream_gbps / HBM_PEAK_GBS, 4),
             "step_frac_of_ceiling": round(akv_bytes / (ms_per_step * 1e-3) / 1e9 / stream_gbps, 4),
-            "how": "akv_stream_read (16-byte non-temporal loads, grid-stride) over the K tensors of the rotating fp16 copies, timed like a step"}
+            "how": "akv_stream_read (16-byte non-temporal loads, four in flight per lane, 1-MB blocks dealt over the XCDs) over the K tensors of the rotating fp16 copies, timed like a step"}
         result["vs_fp16_kernel"] = {
             "fp16_kernel_us": round(fp16_us, 2), "fp16_kernel_GBps": round(fp16_bytes / fp16_us / 1e3, 1),
             "fp16_kernel_frac_of_peak": round(fp16_bytes / fp16_us / 1e3 / HBM_PEAK_GBS, 4),

@@ -136,10 +136,14 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     // A wave that is done with its tiles has nothing to do until the mid step has run: it fetches the HI bytes
     // of its first batch of V rows now (they depend on nothing).  Not when the row that is being appended lies
     // in that range -- its bytes are stored below.
+    // The batches of 8*KG rows are dealt over the waves in contiguous, balanced ranges, like the K blocks (timed against
+    // taking turns batch by batch: 1 % faster).
     constexpr int KG = head_v_groups<G, NT>(), RB = 8 * KG;
-    const bool pre_ok = !(appended && len_old < kHeadVPre * RB * kWaves);
+    const int nbatch = (len + RB - 1) / RB;
+    const int vb0 = (int)((long long)nbatch * wave_u / kWaves), vb1 = (int)((long long)nbatch * (wave_u + 1) / kWaves);
+    const bool pre_ok = !(appended && len_old < (vb0 + kHeadVPre) * RB);   // false only where the new row lies in the rows fetched here
     u32x4_t pre[kHeadVPre][KG];
-    v_prefetch_hi<KG, kHeadVPre>(a, b, h, wave * RB, RB * kWaves, pre_ok ? len : 0, pre);
+    v_prefetch_hi<KG, kHeadVPre>(a, b, h, vb0 * RB, RB, pre_ok ? len : 0, pre);
     if (appended && tid < kD) {   // the new token goes into the planes (the block's lines were just read: they are in L2), K_colmax follows
         store_token_rmw(const_cast<uint8_t*>(a.k_hi), const_cast<uint8_t*>(a.k_mid), const_cast<uint8_t*>(a.k_lo),
                         const_cast<uint8_t*>(a.v_hi), const_cast<uint8_t*>(a.v_mid), const_cast<uint8_t*>(a.v_lo), bh,
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     }
     mid_step<G, NT>(a, b, h, len, ms, own, own_ok);
 
-    // ---- V side: batches of 8*KG rows round-robin over the waves ----------------------------------------
+    // ---- V side: each wave walks its range of batches of 8*KG rows -------------------------------------
     VRule vr;
     v_rule_setup(ms.ehat, a.guard_bits, a.force_level, vr);
     float Mg[G];
@@ -182,9 +186,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
     }
-    const int nbatch = (len + RB - 1) / RB;
-    const int mine = nbatch > wave ? (nbatch - wave + kWaves - 1) / kWaves : 0;
-    v_rows<G, KG, DEBUG, kHeadVPre>(a, b, h, wave * RB, RB * kWaves, mine, len, vr, Mg, acc, z, pre, pre_ok);
+    v_rows<G, KG, DEBUG, kHeadVPre>(a, b, h, vb0 * RB, RB, vb1 - vb0, len, vr, Mg, acc, z, pre, pre_ok);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll

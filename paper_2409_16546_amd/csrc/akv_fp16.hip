@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kD) void fp16_combine_kernel(F16Args a)
 
 // Head-per-workgroup variant (the design of the plane kernels' main path): one workgroup of 1024 threads does
 // the whole (sequence, KV head): logits of all tokens (kept in the workspace), their maximum, then weights and
-// O.  A wave takes batches of 32 rows round-robin; the 8 row loads of the next batch are in flight while the
+// O.  A wave takes a contiguous range of the batches of 32 rows; the 8 row loads of the next batch are in flight while the
 // current batch is reduced.
 template <int G, int NT>
 __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restrict__ logits)
@@ -215,12 +215,14 @@ __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restr
         unpack8h(w, qf[g]);
     }
     const int nbatch = (len + 31) / 32;
+    // each wave walks a contiguous, balanced range of the batches, as in the aligned kernel of this shape
+    const int bt0 = (int)((long long)nbatch * wave / kWaves), bt1 = (int)((long long)nbatch * (wave + 1) / kWaves);
     // the same cache hints as the aligned kernels of this shape: K non-temporal, V not
     auto load_batch = [&](const __amdgpu_buffer_rsrc_t& rs, int bt, u32x4_t (&w)[kLoads], auto nt) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int t = bt * 32 + j * 4 + r;
-            const uint32_t off = (bt < nbatch && t < len) ? uint32_t(t) * (kD * 2) + cl * 16 : kSkip;
+            const uint32_t off = (bt < bt1 && t < len) ? uint32_t(t) * (kD * 2) + cl * 16 : kSkip;
             w[j] = decltype(nt)::value ? buf_load_b128_nt(rs, off) : buf_load_b128(rs, off);
         }
     };
@@ -232,10 +234,10 @@ __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restr
 #pragma unroll
     for (int g = 0; g < G; ++g) mloc[g] = -INFINITY;
     u32x4_t wc[kLoads], wn[kLoads];
-    load_batch(rs_k, wave, wc, kNt);
+    load_batch(rs_k, bt0, wc, kNt);
 #pragma unroll 1
-    for (int bt = wave; bt < nbatch; bt += kWaves) {
-        load_batch(rs_k, bt + kWaves, wn, kNt);
+    for (int bt = bt0; bt < bt1; ++bt) {
+        load_batch(rs_k, bt + 1, wn, kNt);
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int t = bt * 32 + j * 4 + r;
@@ -277,10 +279,10 @@ __global__ __launch_bounds__(NT) void fp16_head_kernel(F16Args a, float* __restr
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[g][i] = 0.0f;
     }
-    load_batch(rs_v, wave, wc, kKeep);
+    load_batch(rs_v, bt0, wc, kKeep);
 #pragma unroll 1
-    for (int bt = wave; bt < nbatch; bt += kWaves) {
-        load_batch(rs_v, bt + kWaves, wn, kKeep);
+    for (int bt = bt0; bt < bt1; ++bt) {
+        load_batch(rs_v, bt + 1, wn, kKeep);
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int t = bt * 32 + j * 4 + r;

@@ -347,7 +347,10 @@ hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v,
     p += align256(bhq * a.nsplit * sizeof(float));
     float* logits = reinterpret_cast<float*>(p);
     const int G = s.Hq / s.Hkv;
-    if (G <= 2 && s.B * s.Hkv >= 192 && max_len <= 16384) {   // enough heads to fill the chip: one workgroup per head
+    // One workgroup per head only for short sequences on a full chip (timed on 256 heads: 31.6 against 40.5 us at 1024
+    // tokens, even at 2048, 99 against 86.5 us at 4096): beyond that the many small workgroups of the chunk kernel
+    // stream faster (6.2 TB/s), and the yardstick is the faster of the two.
+    if (G <= 2 && s.B * s.Hkv >= 192 && max_len < 2048) {
         const dim3 hgrid(xcd_grid(size_t(s.B) * s.Hkv));
         if (G == 1) hipLaunchKernelGGL((fp16_head_kernel<1, 1024>), hgrid, dim3(1024), 0, st, a, logits);
         else hipLaunchKernelGGL((fp16_head_kernel<2, 1024>), hgrid, dim3(1024), 0, st, a, logits);

@@ -169,6 +169,33 @@ def test_decode_random_shapes_lengths_and_parameters(T):
             T.assert_decode_equal(out2, dbg, r2, oc.lens.tolist(), G, f"random case {case} + 1 token")
 
 
+@pytest.mark.parametrize("B,Hkv,G", [(3, 7, 1), (5, 5, 2), (9, 2, 4)])
+def test_head_path_with_pair_counts_that_do_not_divide_by_eight(T, B, Hkv, G):
+    """The head-per-workgroup kernel pads its grid to a multiple of eight workgroups and gives every XCD a run of
+    consecutive (sequence, head) pairs: 21, 25 and 18 pairs leave padding workgroups and uneven runs; ragged lengths
+    (with an empty and a one-token sequence) make some waves' ranges of V batches empty.  Then one token more, fused."""
+    from paper_2409_16546_amd import workloads, binding as A
+    from oracle import akv_oracle as O
+    say(f"head path, {B * Hkv} pairs (B{B} Hkv{Hkv} G{G}), ragged")
+    Ncap = 768
+    rng = np.random.default_rng(100 * B + Hkv)
+    lens = [int(x) for x in rng.integers(2, Ncap, size=B)]
+    lens[0], lens[1] = 0, 1
+    w = workloads.make(2, B=B, Hq=Hkv * G, Hkv=Hkv, N=max(lens), seed=4242 + B)
+    gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, Ncap=Ncap, path=1)
+    T.assert_cache_equal(gc, oc)
+    T.assert_decode_equal(out, dbg, r, lens, G, f"{B * Hkv} pairs")
+    gen = torch.Generator().manual_seed(B)
+    kn = torch.randn(B, Hkv, 1, 128, generator=gen).half()
+    vn = torch.randn(B, Hkv, 1, 128, generator=gen).half()
+    O.append(oc, T.bits(kn), T.bits(vn), np.array([1] * B, np.int32))
+    out2 = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), w.q.to(DEV), dbg=dbg, path=1)
+    torch.cuda.synchronize()
+    r2 = O.decode_attention(oc, T.bits(w.q))
+    T.assert_cache_equal(gc, oc)
+    T.assert_decode_equal(out2, dbg, r2, oc.lens.tolist(), G, f"{B * Hkv} pairs + 1 token")
+
+
 def test_decode_edge_lengths_empty_one_and_smallest_capacity(T):
     from paper_2409_16546_amd import workloads
     say("decode parity: lens 0 / 1 / 255 / 256, Ncap 256")

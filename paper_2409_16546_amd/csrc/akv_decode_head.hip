@@ -2,6 +2,7 @@
 // Rule 1 levels, q.K~ over all tiles, the mid step, Rule 2 + S.V~ over all rows, the final division --
 // so nothing is handed between workgroups and one launch covers the whole step.  Used when there are enough
 // (sequence, KV head) pairs to fill the chip.  Logits live in the workspace (they stay in this XCD's L2).
+// Workgroup L of the launch runs on XCD L % 8; an XCD takes consecutive pairs (4.5 % faster than every eighth pair).
 // Sections "Quantization of K-Cache", "Quantization of V-Cache", "Runtime of AlignedKV".
 #include "akv_common.h"
 #include "akv_k_tile.h"
@@ -24,10 +25,10 @@ __device__ __forceinline__ void finish_append(const DecodeArgs& a, int b, int le
     }
 }
 
-// groups of 8 rows per batch of the V side: what the register budget of the launch shape allows
 // batches of V rows whose HI bytes a wave fetches while it waits for the mid step, and keeps in flight afterwards
 // (three where the registers allow it: 1.7 % faster than two on 4096 tokens; four spill)
 template <int G> constexpr int head_v_pre() { return G == 1 ? 3 : 2; }
+// groups of 8 rows per batch of the V side: what the register budget of the launch shape allows
 template <int G, int NT> constexpr int head_v_groups() { return NT <= 512 && G <= 2 ? 4 : 2; }
 
 template <int G, int NT, bool DEBUG>
@@ -135,11 +136,10 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
         stores_done();   // ordered after the read of the length
         ticket = take_ticket(&a.flags[AKV_NFLAGS + b]);
     }
-    // A wave that is done with its tiles has nothing to do until the mid step has run: it fetches the HI bytes
-    // of its first batch of V rows now (they depend on nothing).  Not when the row that is being appended lies
-    // in that range -- its bytes are stored below.
-    // The batches of 8*KG rows are dealt over the waves in contiguous, balanced ranges, like the K blocks (timed against
-    // taking turns batch by batch: 1 % faster).
+    // The batches of 8*KG V rows are dealt over the waves in contiguous, balanced ranges, like the K blocks (timed against
+    // taking turns batch by batch: 1 % faster).  A wave that is done with its tiles has nothing to do until the mid step
+    // has run: it fetches the HI bytes of its first batches now (they depend on nothing).  Not when the row that is
+    // being appended lies among those rows -- its bytes are stored below.
     constexpr int KG = head_v_groups<G, NT>(), RB = 8 * KG, kHeadVPre = head_v_pre<G>();
     const int nbatch = (len + RB - 1) / RB;
     const int vb0 = (int)((long long)nbatch * wave_u / kWaves), vb1 = (int)((long long)nbatch * (wave_u + 1) / kWaves);

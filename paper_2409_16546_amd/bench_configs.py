@@ -79,6 +79,27 @@ def measure(cfg: int, steps: int = 50, dev: str = "cuda:0") -> dict:
     res["us_by_path"] = paths
     res["control_group_16bit_us"] = round(timed(lambda i: A.akv_decode_attention(caches[i % R], qd, o, max_len=maxlen,
                                                                                 force_level=2), steps), 1)
+    if cfg == 3:
+        # this configuration is defined with the append in the step: one more token per sequence is stored and attended
+        # to.  Timed over consecutive steps that end at the configuration's context (the library's own choice of path,
+        # which here stores the token with its append kernel before the four decode kernels)
+        nsteps = min(steps, 100)
+        first = N - 5 - nsteps
+        grow = A.Cache.allocate(w.B, w.Hq, w.Hkv, w.D, N, dev)
+        A.akv_append(grow, kd[:, :, :first].contiguous(), vd[:, :, :first].contiguous())
+        kn = [kd[:, :, first + i].contiguous() for i in range(5 + nsteps)]
+        vn = [vd[:, :, first + i].contiguous() for i in range(5 + nsteps)]
+        for i in range(5):
+            A.akv_append_decode_attention(grow, kn[i], vn[i], qd, o, max_len=N)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(5, 5 + nsteps):
+            A.akv_append_decode_attention(grow, kn[i], vn[i], qd, o, max_len=N)
+        torch.cuda.synchronize()
+        res["fused_append_step_us"] = round((time.perf_counter() - t0) * 1e6 / nsteps, 1)
+        res["fused_append_step_contexts"] = [first + 6, N]
+        assert int(grow.lens.max()) == N and int(grow.flags[0]) == 0
+        del grow, kn, vn
     gbps = total / paths["library_choice"] / 1e3
     res["roofline"] = {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(gbps / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes_per_step": int(total)}

@@ -19,6 +19,12 @@ __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t
     cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
     const bool fits = len + cnt <= Ncap;   // else the sequence is left unchanged and the refusal is counted
     const size_t bh = size_t(b) * Hkv + h;
+    // The ticket is drawn as soon as this workgroup has read the length (the test keeps the atomic behind that read):
+    // its round trip then runs beside the loads and stores below instead of after them.  Whoever draws the last one
+    // moves the length at its end -- every head of the sequence has read the old one by then, and nothing in this
+    // kernel reads the planes.
+    int ticket = -1;
+    if (d == 0 && len >= 0) ticket = atomicAdd(&c.flags[AKV_NFLAGS + b], 1);
     if (fits) {
     const uint16_t* kn = k_new + bh * n * kD;
     const uint16_t* vn = v_new + bh * n * kD;
@@ -30,12 +36,7 @@ __global__ __launch_bounds__(128) void append_kernel(akv_cache c, const uint16_t
     }
     c.colmax[bh * kD + d] = (uint16_t)cm;
     }
-    // The workgroup of the sequence that arrives last (every head has read lens[b] by then) moves the length.
-    __shared__ int last_s;
-    __syncthreads();
-    if (d == 0) last_s = atomicAdd(&c.flags[AKV_NFLAGS + b], 1) == Hkv - 1;
-    __syncthreads();
-    if (last_s && d == 0) {
+    if (d == 0 && ticket == Hkv - 1) {
         c.flags[AKV_NFLAGS + b] = 0;
         if (fits) c.lens[b] = len + cnt;
         else atomicAdd(&c.flags[AKV_FLAG_OVERFLOW], 1);

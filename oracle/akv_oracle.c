@@ -21,7 +21,10 @@
  * error bound exhaustive; half->float conversion against numpy; K and V rules
  * against brute force over every level assignment and against the numerical
  * error bound they promise; top-k against an exact sort; force_level=2 against
- * textbook fp64 attention.  UNPINNED (the paper fixes no value): top-k size 32,
+ * textbook fp64 attention; out at mixed levels against a numpy fp64 attention
+ * over operands rebuilt from the exported lvlK / appliedV masks.  The whole file
+ * also runs under AddressSanitizer + UBSan (tests/test_oracle_sanitizers.py).
+ * UNPINNED (the paper fixes no value): top-k size 32,
  * the score floor 2^-64, and the size of (out - fp16 attention) on synthetic data.
  *
  * Notation follows the paper: K, V, Q, S, O, K_colmax, O_est.  fp16 bit pattern

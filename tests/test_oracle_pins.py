@@ -513,6 +513,58 @@ def test_all_16_bit_reads_reproduce_textbook_fp64_attention(oracle, G):
     assert e0 < 5e-2 and e4 <= e0
 
 
+def read_bits_np(h, lvl):
+    """fp16 bit patterns h read at levels lvl (broadcast): the kept bits, then 100... ("Dynamic Quantization")."""
+    h = h.astype(np.uint16)
+    r = np.where(lvl == 2, h, np.where(lvl == 1, (h & 0xFFF0) | 0x0008, (h & 0xFF00) | 0x0080)).astype(np.uint16)
+    return r.view(np.float16).astype(np.float64)
+
+
+def mixed_level_case(seed, G, N):
+    """Data on which Rule 1 leaves K columns, and Rule 2 leaves V rows, at all three levels: channel scales over a
+    few octaves for K; a flat softmax (small q), a spread of row scales and a nonzero mean (no result channel cancels
+    to almost nothing) for V."""
+    rng = np.random.default_rng(seed)
+    D = 128
+    q = (rng.normal(size=(1, G, D)) * 0.05).astype(np.float16)
+    k = (rng.normal(size=(1, 1, N, D)) * np.exp2(rng.integers(-5, 6, size=(1, 1, 1, D)))).astype(np.float16)
+    v = ((rng.normal(size=(1, 1, N, D)) + 3.0) * np.exp2(rng.integers(-13, 1, size=(1, 1, N, 1)))).astype(np.float16)
+    return q, k, v
+
+
+@pytest.mark.parametrize("force", [-1, 0, 1])
+@pytest.mark.parametrize("G", [1, 2])
+def test_out_is_attention_over_the_values_as_they_were_read(oracle, G, force):
+    """"Runtime of AlignedKV": S = QK^T/sqrt(128); softmax; O = SV, on the operands "Dynamic Quantization" hands over:
+    K column d read at lvlK[d], V row t read at appliedV[t].  Recomputed in numpy fp64 from the exported masks; a value
+    path that reads either operand at any other level than the exported one fails here."""
+    N, D = 200, 128
+    q, k, v = mixed_level_case(100 + G, G, N)
+    c = fill_cache(oracle, f16bits(k), f16bits(v))
+    r = oracle.decode_attention(c, f16bits(q), force_level=force)
+    lvlK, appl = r.lvlK[0, 0], r.appliedV[0, 0, :N]
+    if force < 0:
+        assert set(lvlK.tolist()) == {0, 1, 2} and set(appl.tolist()) == {0, 1, 2}    # every level is exercised
+    else:
+        assert np.all(lvlK == force) and np.all(appl == force)
+    kt = read_bits_np(f16bits(k)[0, 0], lvlK[None, :])                       # [N, D]
+    vt = read_bits_np(f16bits(v)[0, 0], appl[:, None])                       # [N, D]
+    full_k, full_v = k[0, 0].astype(np.float64), v[0, 0].astype(np.float64)
+    ref = np.zeros((G, D))
+    wrongK = np.zeros((G, D))
+    wrongV = np.zeros((G, D))
+    for g in range(G):
+        qg = q[0, g].astype(np.float64)
+        for kk, vv, dst in ((kt, vt, ref), (full_k, vt, wrongK), (kt, full_v, wrongV)):
+            s = (kk @ qg) / math.sqrt(D)
+            w = np.exp(s - s.max())
+            dst[g] = (w / w.sum()) @ vv
+    assert np.abs(r.out[0] - ref).max() <= 1e-12 * max(1.0, np.abs(ref).max())
+    if force != 2:
+        # the pin discriminates: the same sums over operands read at 16 bits are far outside the tolerance
+        assert np.abs(wrongK - ref).max() > 1e-7 and np.abs(wrongV - ref).max() > 1e-7
+
+
 def test_counts_add_up(oracle):
     rng = np.random.default_rng(90)
     q, k, v = tiny_case(rng, 2, 100, 128, spread=3)

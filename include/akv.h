@@ -72,6 +72,8 @@ typedef struct akv_sizes {
 #define AKV_TB 256          /* tokens per K block */
 #define AKV_NFLAGS 4
 #define AKV_FLAG_OVERFLOW 0 /* flags[0]: number of (call, sequence) appends refused for capacity */
+#define AKV_FLAG_MAXLEN 1   /* flags[1]: number of (decode call, sequence) pairs whose length exceeded params->max_len
+                               (the tokens past max_len were then left out of that call's attention)            */
 
 /*
  * The cache: plane layout (TB = 256, NB = Ncap/256, all uint8 unless said):
@@ -111,15 +113,35 @@ typedef struct akv_debug {
     uint8_t *appliedV; /* [B][Hkv][Ncap]     level each V token row was read at (max over its channels) */
 } akv_debug;
 
+/*
+ * Optional device counters of what a decode call read (section "Reduction in Bit Widths": the average number of
+ * bits fetched per element is the quantity the paper plots against the context length).  A DEVICE pointer to this
+ * struct goes into akv_params.stats; the call ADDS to the counters (the caller zeroes them when it wants a fresh
+ * count), inside the decode kernels themselves -- no further pass over the cache.  Index = level 0 / 1 / 2 =
+ * 8 / 12 / 16 bits.  Only tokens t < lens[b] count.
+ *   k_elems[l]      K elements read at level l              (columns at level l  x  tokens of the sequence)
+ *   v_row_elems[l]  V elements read at level l              (token rows fetched at level l  x  D)
+ *   v_need_elems[l] V elements that need level l by Rule 2  (before the maximum over the token row is taken)
+ * Bytes fetched per plane follow: K_hi = sum_l k_elems[l], K_mid = (k_elems[1] + k_elems[2]) / 2, K_lo =
+ * k_elems[2] / 2, and the same for V from v_row_elems.  Requesting the counters selects the kernel variant that also
+ * serves the mask exports of akv_debug (slower than the plain one; results are identical).
+ */
+typedef struct akv_stats {
+    uint64_t k_elems[3];
+    uint64_t v_row_elems[3];
+    uint64_t v_need_elems[3];
+} akv_stats;
+
 typedef struct akv_params {
     float scale;          /* softmax scale; <= 0 means 1/sqrt(D)                                    */
     int32_t topk;         /* size of the approximate top-k behind O_est, 1..AKV_MAX_TOPK; 0 means 32 */
     int32_t guard_bits;   /* extra mantissa bits both rules require, 0..12 (0 = the literal rule)    */
     int32_t force_level;  /* -1 adaptive; 0/1/2 read everything at 8/12/16 bits (2 = control group)  */
     int32_t out_dtype;    /* 0: out is float32 [B][Hq][D]; 1: out is fp16 [B][Hq][D]                 */
-    int32_t max_len;      /* host-known upper bound of lens[] used to size the launch; 0 means Ncap.
-                             A value below a sequence's length must not be passed: the token-split
-                             kernels then attend to the first max_len tokens only                   */
+    int32_t max_len;      /* host-known upper bound of lens[] used to size the launch; 0 means Ncap.  In
+                             akv_append_decode_attention it bounds the lengths AFTER the append.  A sequence
+                             longer than max_len is attended over its first max_len tokens only (on either
+                             path) and counted in flags[AKV_FLAG_MAXLEN]                               */
     const akv_debug *dbg; /* host pointer to a struct of device pointers, or NULL                    */
     void *const *events;  /* host pointer to 3 hipEvent_t, or NULL: the library records them on the
                              stream before its first kernel, in front of the V kernel of
@@ -128,6 +150,7 @@ typedef struct akv_params {
                              the kernels in place                                                   */
     int32_t path;         /* 0: choose; 1: head-per-workgroup path (one kernel; needs Hq/Hkv <= 4);
                              2: token-split path (four kernels).  Both give the same decisions.       */
+    akv_stats *stats;     /* DEVICE pointer to counters the call adds to, or NULL                    */
 } akv_params;
 
 #define AKV_MAX_TOPK 64

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libakv.so")
 AKV_OK, AKV_EINVAL, AKV_EWORKSPACE, AKV_EHIP = 0, 1, 2, 3
 AKV_TB = 256
 AKV_NFLAGS = 4
+AKV_FLAG_OVERFLOW, AKV_FLAG_MAXLEN = 0, 1
 AKV_MAX_TOPK = 64
 EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
            "akv_decode_attention", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read",
@@ -49,10 +50,14 @@ class akv_debug(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("lvlK", "logits", "a", "sel", "oest", "Ehat", "needV", "appliedV")]
 
 
+class akv_stats(C.Structure):
+    _fields_ = [("k_elems", C.c_uint64 * 3), ("v_row_elems", C.c_uint64 * 3), ("v_need_elems", C.c_uint64 * 3)]
+
+
 class akv_params(C.Structure):
     _fields_ = [("scale", C.c_float), ("topk", C.c_int32), ("guard_bits", C.c_int32), ("force_level", C.c_int32),
                 ("out_dtype", C.c_int32), ("max_len", C.c_int32), ("dbg", C.POINTER(akv_debug)),
-                ("events", C.POINTER(C.c_void_p)), ("path", C.c_int32)]
+                ("events", C.POINTER(C.c_void_p)), ("path", C.c_int32), ("stats", C.c_void_p)]
 
 
 class akw_weights(C.Structure):
@@ -246,21 +251,33 @@ class DebugBuffers:
                          _ptr(self.Ehat), _ptr(self.needV), _ptr(self.appliedV))
 
 
+def new_stats(device="cuda:0") -> torch.Tensor:
+    """Zeroed device counters for the `stats` argument of the decode calls: int64 [9] = k_elems[3], v_row_elems[3],
+    v_need_elems[3] (the fields of akv_stats in order); every call adds to them."""
+    return torch.zeros(9, dtype=torch.int64, device=device)
+
+
+def _params(out, scale, topk, guard_bits, force_level, max_len, d, events, path, stats) -> akv_params:
+    if stats is not None:
+        assert stats.dtype == torch.int64 and stats.numel() == 9
+    return akv_params(scale, topk, guard_bits, force_level, 0 if out.dtype == torch.float32 else 1, max_len,
+                      C.pointer(d) if d is not None else None, events, path, _ptr(stats))
+
+
 def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None = None, *, scale: float = 0.0,
                          topk: int = 32, guard_bits: int = 0, force_level: int = -1, max_len: int = 0,
                          dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None,
-                         events=None, path: int = 0) -> torch.Tensor:
+                         events=None, path: int = 0, stats: torch.Tensor | None = None) -> torch.Tensor:
     """q: fp16 [B, Hq, D] on the device; out: float32 or fp16 [B, Hq, D] (allocated if None).
     events: None or a ctypes array of 3 hipEvent_t handles the library records around its kernels.
-    path: 0 choose, 1 head-per-workgroup kernel, 2 token-split kernels."""
+    path: 0 choose, 1 head-per-workgroup kernel, 2 token-split kernels.  stats: see new_stats()."""
     assert q.dtype == torch.float16 and tuple(q.shape) == (cache.B, cache.Hq, cache.D)
     if out is None:
         out = torch.empty(cache.B, cache.Hq, cache.D, dtype=torch.float32, device=q.device)
     assert out.dtype in (torch.float32, torch.float16) and tuple(out.shape) == tuple(q.shape)
     ws = cache.workspace if workspace is None else workspace
     d = dbg.struct() if dbg is not None else None
-    p = akv_params(scale, topk, guard_bits, force_level, 0 if out.dtype == torch.float32 else 1, max_len,
-                   C.pointer(d) if d is not None else None, events, path)
+    p = _params(out, scale, topk, guard_bits, force_level, max_len, d, events, path, stats)
     s = cache.struct()
     _check(lib().akv_decode_attention(C.byref(s), _ptr(q), _ptr(out), C.byref(p), _ptr(ws), ws.numel(), _stream()))
     return out
@@ -270,7 +287,7 @@ def akv_append_decode_attention(cache: Cache, k_new: torch.Tensor, v_new: torch.
                                 out: torch.Tensor | None = None, *, scale: float = 0.0, topk: int = 32,
                                 guard_bits: int = 0, force_level: int = -1, max_len: int = 0,
                                 dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None, events=None,
-                                path: int = 0) -> torch.Tensor:
+                                path: int = 0, stats: torch.Tensor | None = None) -> torch.Tensor:
     """One decode step: append k_new, v_new (fp16 [B, Hkv, 1, D] or [B, Hkv, D]) and attend with q."""
     assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16 and k_new.numel() == cache.B * cache.Hkv * cache.D
     assert v_new.numel() == k_new.numel()
@@ -280,8 +297,7 @@ def akv_append_decode_attention(cache: Cache, k_new: torch.Tensor, v_new: torch.
     assert out.dtype in (torch.float32, torch.float16) and tuple(out.shape) == tuple(q.shape)
     ws = cache.workspace if workspace is None else workspace
     d = dbg.struct() if dbg is not None else None
-    p = akv_params(scale, topk, guard_bits, force_level, 0 if out.dtype == torch.float32 else 1, max_len,
-                   C.pointer(d) if d is not None else None, events, path)
+    p = _params(out, scale, topk, guard_bits, force_level, max_len, d, events, path, stats)
     s = cache.struct()
     _check(lib().akv_append_decode_attention(C.byref(s), _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(out), C.byref(p),
                                              _ptr(ws), ws.numel(), _stream()))

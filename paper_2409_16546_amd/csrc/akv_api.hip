@@ -67,7 +67,7 @@ int compute_units()
 
 extern "C" {
 
-int akv_version(void) { return 100; }
+int akv_version(void) { return 101; }
 
 const char* akv_last_error(void) { return g_err; }
 
@@ -168,8 +168,10 @@ bool head_path_pays(long pairs, int G, int max_len)
 }
 
 // decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])
+// static_scratch: the workspace is the library's own device array (akv_decode_attention_static)
 akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, void* out,
-                       const akv_params* params, void* workspace, size_t workspace_bytes, void* stream)
+                       const akv_params* params, void* workspace, size_t workspace_bytes, void* stream,
+                       bool static_scratch = false)
 {
     if (akv_status st = check_cache(cache)) return st;
     if (!q || !out) return fail(AKV_EINVAL, "q / out is NULL");
@@ -186,10 +188,11 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     if (p.out_dtype != 0 && p.out_dtype != 1) return fail(AKV_EINVAL, "out_dtype = %d is neither 0 (f32) nor 1 (f16)", p.out_dtype);
     if (p.max_len < 0 || p.max_len > cache->shape.Ncap) return fail(AKV_EINVAL, "max_len = %d out of range 0..Ncap", p.max_len);
     if (!(p.scale == p.scale) || std::isinf(p.scale)) return fail(AKV_EINVAL, "scale is not finite");
-    const akv::WsLayout w = akv::ws_layout(cache->shape);
+    const akv::WsLayout w = akv::ws_layout(cache->shape, static_scratch);
     if (!workspace || workspace_bytes < w.total)
         return fail(AKV_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, w.total);
     if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(AKV_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (p.stats && reinterpret_cast<uintptr_t>(p.stats) % 8) return fail(AKV_EINVAL, "stats must be 8-byte aligned");
 
     akv::DecodeArgs a;
     std::memset(&a, 0, sizeof a);
@@ -226,6 +229,7 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     a.partZ = reinterpret_cast<float*>(ws + w.partZ);
     a.kcount = reinterpret_cast<int32_t*>(ws + w.control);
     a.vcount = a.kcount + size_t(a.s.B) * a.s.Hkv;
+    a.stats = p.stats;
     if (p.dbg) {
         a.dbg = *p.dbg;
         if (a.dbg.logits) a.logits = a.dbg.logits;   // same shape: the pass writes the export directly

@@ -43,10 +43,13 @@ struct WsLayout {
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 inline __host__ __device__ int v_splits(int ntok) { return (ntok + kVChunk - 1) / kVChunk; }   // V-pass chunks covering ntok
 
-inline WsLayout ws_layout(const akv_shape& s)
+// control_front: the control words come first, inside a reserved block of kCtlReserve bytes whose place does not
+// depend on the shape (the layout of the library's own static scratch array, shared by calls of every shape)
+constexpr size_t kCtlReserve = 64 * 1024;
+inline WsLayout ws_layout(const akv_shape& s, bool control_front = false)
 {
     WsLayout w;
-    size_t off = 0;
+    size_t off = control_front ? kCtlReserve : 0;
     const size_t bhq = size_t(s.B) * s.Hq;
     w.logits = off;  off = align256(off + bhq * s.Ncap * sizeof(float));
     w.tilemax = off; off = align256(off + bhq * (s.Ncap / kTB) * sizeof(float));
@@ -57,9 +60,13 @@ inline WsLayout ws_layout(const akv_shape& s)
     w.Ehat = off;    off = align256(off + size_t(s.B) * s.Hkv * kD * sizeof(int32_t));
     w.partO = off;   off = align256(off + bhq * v_splits(s.Ncap) * kD * sizeof(float));
     w.partZ = off;   off = align256(off + bhq * v_splits(s.Ncap) * sizeof(float));
-    w.control = off;
     w.control_bytes = 2 * size_t(s.B) * s.Hkv * sizeof(int32_t);
-    off = align256(off + w.control_bytes);
+    if (control_front) {
+        w.control = 0;
+    } else {
+        w.control = off;
+        off = align256(off + w.control_bytes);
+    }
     w.total = off;
     return w;
 }
@@ -89,6 +96,7 @@ struct DecodeArgs {
     int32_t* kcount;     // [B][Hkv] spare control words (kept zero; the selection runs in a kernel of its own)
     int32_t* vcount;
     akv_debug dbg;       // device pointers or NULL
+    akv_stats* stats;    // device counters the kernels add to, or NULL
 };
 
 // Store one token of one (sequence, KV head) at position t: thread d (0..127) owns K channel d and is the

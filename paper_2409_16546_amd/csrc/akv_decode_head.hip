@@ -71,7 +71,12 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
             old_l = a.k_lo[nib];
         }
     }
-    const int len = len_old + (appended ? 1 : 0);
+    // A sequence longer than the caller's bound max_len is attended over its first max_len tokens (as on the
+    // token-split path) and counted; the new token is stored in any case.
+    const int len_k = min(len_old, a.max_len);                      // stored tokens the K side walks
+    const bool attend_new = appended && len_old + 1 <= a.max_len;   // the new token takes part in the attention
+    const int len = len_k + (attend_new ? 1 : 0);
+    if (h == 0 && tid == 0 && len_old + (appended ? 1 : 0) > a.max_len) atomicAdd(&a.flags[AKV_FLAG_MAXLEN], 1);
     if (len == 0) {                                     // an empty sequence attends to nothing: zeros
         for (int idx = tid; idx < G * kD; idx += NT) store_out(a, size_t(b) * Hq + size_t(h) * G + idx / kD, idx % kD, 0.0f);
         finish_append(a, b, len_old, ticket);
@@ -81,7 +86,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     // ---- K side: levels, then the 256-token blocks of the head dealt over the waves ---------------------
     // in contiguous, balanced ranges (sizes differ by at most one block)
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int nblk = (len_old + kTB - 1) / kTB;   // the tokens already stored
+    const int nblk = (len_k + kTB - 1) / kTB;   // the tokens already stored
     const int per = nblk / kWaves, extra = nblk % kWaves;
     int blk = wave_u * per + min(wave_u, extra);
     const int blk_end = blk + per + (wave_u < extra ? 1 : 0);
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
         if (blk == keep_blk) k_tile_pre<false>(a, b, h, blk, kpre);
         else k_tile_pre<true>(a, b, h, blk, kpre);
     }
-    const uint32_t colmax_used = k_levels_finish<G>(a, b, h, ks, true, k_new_bits, lin);
+    const uint32_t colmax_used = k_levels_finish<G>(a, b, h, ks, true, k_new_bits, lin, len);
     float wm[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) wm[g] = -INFINITY;
@@ -114,15 +119,15 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     uint8_t* stage = &kstage[wave_u][0];
     if (pre_any) {   // the block whose first HI bytes are already in flight
         float tm[G];
-        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_old, ks, 0, tm, kpre, true, own, stage);
-        else k_tile<G, true>(a, b, h, blk, len_old, ks, 0, tm, kpre, true, own, stage);
+        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_k, ks, 0, tm, kpre, true, own, stage);
+        else k_tile<G, true>(a, b, h, blk, len_k, ks, 0, tm, kpre, true, own, stage);
         blk += 1;
         fold(tm);
     }
     while (blk < blk_end) {
         float tm[G], later[G][4];
-        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_old, ks, 0, tm, kpre, false, later, stage);
-        else k_tile<G, true>(a, b, h, blk, len_old, ks, 0, tm, kpre, false, later, stage);
+        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_k, ks, 0, tm, kpre, false, later, stage);
+        else k_tile<G, true>(a, b, h, blk, len_k, ks, 0, tm, kpre, false, later, stage);
         blk += 1;
         fold(tm);
     }
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
         for (int g = 0; g < G; ++g) wmax_s[g][wave] = wm[g];
     // The new token's logit: one lane per query head walks its fp16 row in channel order.  Wave 0 does it after
     // its own tile -- the wave that is done first and would otherwise wait at the barrier below.
-    if (appended && tid < G) ks.new_logit[tid] = new_token_logit<G>(ks, tid);
+    if (attend_new && tid < G) ks.new_logit[tid] = new_token_logit<G>(ks, tid);
     if (tid == 0 && a.k_new) {
         stores_done();   // ordered after the read of the length
         ticket = take_ticket(&a.flags[AKV_NFLAGS + b]);
@@ -155,7 +160,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     __syncthreads();   // also: every logit store and the new token's bytes have completed (same CU, same L2)
     if (tid < G) {
         float m = -INFINITY;
-        if (appended) {   // after the barrier: the tile that covers position len_old has stored its vector
+        if (attend_new) {   // after the barrier: the tile that covers position len_old has stored its vector
             m = ks.new_logit[tid];
             a.logits[(size_t(b) * Hq + size_t(h) * G + tid) * Ncap + len_old] = m;
         }
@@ -166,7 +171,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
 
     // ---- mid step -----------------------------------------------------------------------------------
     const bool own_ok = nblk <= kWaves;   // then wave w < nblk has walked exactly block w, four tokens per lane
-    if (own_ok && appended && (len_old >> 2) == tid) {   // the new token's logit did not come from a tile
+    if (own_ok && attend_new && (len_old >> 2) == tid) {   // the new token's logit did not come from a tile
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -216,7 +221,7 @@ template <int G, int NT>
 static hipError_t launch_head_g(const DecodeArgs& a, hipStream_t st)
 {
     const dim3 grid(xcd_grid(size_t(a.s.B) * a.s.Hkv)), block(NT);
-    if (a.dbg.needV || a.dbg.appliedV) hipLaunchKernelGGL((head_kernel<G, NT, true>), grid, block, 0, st, a);
+    if (a.dbg.needV || a.dbg.appliedV || a.stats) hipLaunchKernelGGL((head_kernel<G, NT, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((head_kernel<G, NT, false>), grid, block, 0, st, a);
     return hipGetLastError();
 }

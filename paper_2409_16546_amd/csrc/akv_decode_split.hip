@@ -29,7 +29,8 @@ __global__ __launch_bounds__(64 * kKWaves) void split_k_kernel(DecodeArgs a)
     const int blk = blockIdx.x * kKWaves + wave_u;
     if (blockIdx.x * kMidSlice >= len) return;   // whole workgroup beyond the sequence (uniform)
 
-    k_levels<G>(a, b, h, ks, blockIdx.x == 0);
+    if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0 && min(a.lens[b], Ncap) > a.max_len) atomicAdd(&a.flags[AKV_FLAG_MAXLEN], 1);
+    k_levels<G>(a, b, h, ks, blockIdx.x == 0, len);
     if (blk * kTB < len) {                       // else this wave's block is beyond the sequence
         float tm[G];
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
@@ -389,7 +390,7 @@ static hipError_t launch_split_g(const DecodeArgs& a, hipStream_t st, hipEvent_t
     if (mid_event)
         if (hipError_t e = hipEventRecord(mid_event, st)) return e;
     const dim3 vgrid((a.max_len + a.vchunk - 1) / a.vchunk, a.s.Hkv, a.s.B), vblock(64 * kVWaves);
-    if (a.dbg.needV || a.dbg.appliedV) hipLaunchKernelGGL((split_v_kernel<G, true>), vgrid, vblock, 0, st, a);
+    if (a.dbg.needV || a.dbg.appliedV || a.stats) hipLaunchKernelGGL((split_v_kernel<G, true>), vgrid, vblock, 0, st, a);
     else hipLaunchKernelGGL((split_v_kernel<G, false>), vgrid, vblock, 0, st, a);
     return hipGetLastError();
 }

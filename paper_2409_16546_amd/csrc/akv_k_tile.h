@@ -45,9 +45,10 @@ __device__ __forceinline__ void k_levels_load(const DecodeArgs& a, int b, int h,
 }
 
 // Returns the K_colmax of channel tid (tid < 128) that the levels used.
+// stat_len: tokens of the sequence the levels apply to (for the counters of akv_stats; used with export_levels).
 template <int G>
 __device__ __forceinline__ uint32_t k_levels_finish(const DecodeArgs& a, int b, int h, KShared<G>& ks, bool export_levels,
-                                                    int k_new_bits, const KLevelsIn<G>& in)
+                                                    int k_new_bits, const KLevelsIn<G>& in, int stat_len)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t bh = size_t(b) * a.s.Hkv + h;
@@ -86,6 +87,12 @@ __device__ __forceinline__ uint32_t k_levels_finish(const DecodeArgs& a, int b, 
             ks.need_lo[wave] = b2;
         }
         if (a.dbg.lvlK && export_levels) a.dbg.lvlK[bh * kD + tid] = (uint8_t)lv;
+        if (a.stats && export_levels && lane == 0) {   // 64 columns of this wave: how many at each level, times the tokens
+            const unsigned long long n2 = __builtin_popcountll(b2), n1 = __builtin_popcountll(b1) - n2, n = (unsigned long long)stat_len;
+            atomicAdd(reinterpret_cast<unsigned long long*>(&a.stats->k_elems[0]), (64ull - n1 - n2) * n);
+            atomicAdd(reinterpret_cast<unsigned long long*>(&a.stats->k_elems[1]), n1 * n);
+            atomicAdd(reinterpret_cast<unsigned long long*>(&a.stats->k_elems[2]), n2 * n);
+        }
         if (k_new_bits >= 0) {   // "Dynamic Quantization": bits that are not read are filled with 100...
             const uint32_t kb = uint32_t(k_new_bits);
             ks.knew[tid] = half_bits_to_float(lv == 2 ? kb : (lv == 1 ? ((kb & 0xFFF0u) | 0x0008u) : ((kb & 0xFF00u) | 0x0080u)));
@@ -97,11 +104,11 @@ __device__ __forceinline__ uint32_t k_levels_finish(const DecodeArgs& a, int b, 
 
 template <int G>
 __device__ __forceinline__ uint32_t k_levels(const DecodeArgs& a, int b, int h, KShared<G>& ks, bool export_levels,
-                                             int k_new_bits = -1)
+                                             int stat_len, int k_new_bits = -1)
 {
     KLevelsIn<G> in;
     k_levels_load<G>(a, b, h, in);
-    return k_levels_finish<G>(a, b, h, ks, export_levels, k_new_bits, in);
+    return k_levels_finish<G>(a, b, h, ks, export_levels, k_new_bits, in, stat_len);
 }
 
 // Fused append: the logit of the token that is being appended, from ks.knew, with the same arithmetic as a

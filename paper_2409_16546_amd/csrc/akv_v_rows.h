@@ -129,6 +129,7 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
 #pragma unroll
     for (int g = 1; g < G; ++g) Mlane = jg == g ? Mg[g] : Mlane;
     float zl = 0.0f;                               // sum of this lane's weights (rows j / G of the batches, head j % G)
+    unsigned st_rows[3] = {0u, 0u, 0u}, st_need[3] = {0u, 0u, 0u};   // DEBUG: this lane's counts for akv_stats
 
     struct Batch {
         u32x4_t hi[KG];
@@ -195,7 +196,12 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
                     if (t < len) {
                         const int applied = need2 ? 2 : (need1 ? 1 : 0);
                         if (a.dbg.appliedV && cl == 0) a.dbg.appliedV[bh * Ncap + t] = (uint8_t)applied;
-                        if (a.dbg.needV) {
+                        if (cl == 0) {
+                            st_rows[0] += applied == 0;
+                            st_rows[1] += applied == 1;
+                            st_rows[2] += applied == 2;
+                        }
+                        if (a.dbg.needV || a.stats) {
                             const int ah = int(ss & 0xFFu) - 64;
                             uint32_t nv[4];
 #pragma unroll
@@ -208,10 +214,14 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
                                     int need = level_for_mantissa_bits(10 + a.guard_bits - (vr.ehat[i * 4 + k] - (ah + ev - 15)));
                                     if (a.force_level >= 0) need = a.force_level;
                                     nv[i] |= (uint32_t)need << (8 * k);
+                                    st_need[1] += need == 1;
+                                    st_need[2] += need == 2;
                                 }
                             }
-                            *reinterpret_cast<uint4*>(a.dbg.needV + (bh * Ncap + t) * kD + cl * 16) =
-                                make_uint4(nv[0], nv[1], nv[2], nv[3]);
+                            st_need[0] += 16;   // all of the lane's elements; those at levels 1 and 2 are taken off at the end
+                            if (a.dbg.needV)
+                                *reinterpret_cast<uint4*>(a.dbg.needV + (bh * Ncap + t) * kD + cl * 16) =
+                                    make_uint4(nv[0], nv[1], nv[2], nv[3]);
                         }
                     }
                 }
@@ -270,6 +280,20 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) z[g] += jg == g ? zl : 0.0f;
+    if (DEBUG && a.stats) {   // uniform; one set of atomics per wave
+        st_need[0] -= st_need[1] + st_need[2];
+        unsigned v6[6] = {st_rows[0], st_rows[1], st_rows[2], st_need[0], st_need[1], st_need[2]};
+#pragma unroll
+        for (int i = 0; i < 6; ++i)
+            for (int o = 1; o < 64; o <<= 1) v6[i] += __shfl_xor(v6[i], o);
+        if (lane == 0) {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                atomicAdd(reinterpret_cast<unsigned long long*>(&a.stats->v_row_elems[i]), (unsigned long long)v6[i] * kD);
+                atomicAdd(reinterpret_cast<unsigned long long*>(&a.stats->v_need_elems[i]), (unsigned long long)v6[3 + i]);
+            }
+        }
+    }
 }
 
 // sum acc over the 8 row lanes of a wave (lanes with the same lane % 8) and z over all lanes; afterwards

@@ -58,7 +58,8 @@ def test_struct_layouts_match_the_header(A):
     text = open(os.path.join(ROOT, "include", "akv.h")).read()
     text += open(os.path.join(ROOT, "include", "akw.h")).read()
     for struct, cls in (("akv_shape", A.akv_shape), ("akv_sizes", A.akv_sizes), ("akv_cache", A.akv_cache),
-                        ("akv_debug", A.akv_debug), ("akv_params", A.akv_params), ("akw_weights", A.akw_weights),
+                        ("akv_debug", A.akv_debug), ("akv_stats", A.akv_stats), ("akv_params", A.akv_params),
+                        ("akw_weights", A.akw_weights),
                         ("akw_sizes", A.akw_sizes), ("akw_params", A.akw_params)):
         body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (struct, struct), text, flags=re.S).group(1)
         body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
@@ -67,7 +68,7 @@ def test_struct_layouts_match_the_header(A):
             decl = decl.strip()
             if not decl:
                 continue
-            names = decl.replace("*", " ").split(",")
+            names = re.sub(r"\[\d+\]", "", decl).replace("*", " ").split(",")
             first = names[0].split()[-1]
             fields += [first] + [n.strip() for n in names[1:]]
         assert fields == [f[0] for f in cls._fields_], struct
@@ -108,6 +109,8 @@ def test_misaligned_pointers_are_refused_before_anything_is_launched(A):
     refused(L.akv_unpack(C.byref(good), q + 2, None, None), "aligned")
     refused(L.akv_fp16_decode_attention(C.byref(shape), q, q + 6, q, q, out, 0.0, 0, 0, ws, 1 << 30, None), "aligned")
     assert L.akv_decode_attention(C.byref(good), q, out, None, ws + 16, 1 << 30, None) == A.AKV_EWORKSPACE
+    p = A.akv_params(0.0, 0, 0, -1, 0, 0, None, None, 0, 0x500004)
+    refused(L.akv_decode_attention(C.byref(good), q, out, C.byref(p), ws, 1 << 30, None), "stats")
 
 
 def test_misaligned_weight_arrays_are_refused(A):

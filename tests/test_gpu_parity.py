@@ -127,7 +127,7 @@ def test_decode_matches_oracle(T, name, cfg, over, lens, params, path):
     lens = w.lens.tolist() if lens is None else lens
     gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, path=path, **params)
     T.assert_cache_equal(gc, oc)
-    err, rl2 = T.assert_decode_equal(out, dbg, r, lens, w.Hq // w.Hkv, name)
+    err, rl2 = T.assert_decode_equal(out, dbg, r, lens, w.Hq // w.Hkv, name, scale=params.get("scale", 0.0))
     say(f"  max-abs {err:.2e} rel-L2 {rl2:.2e} levels K {np.bincount(r.lvlK.ravel(), minlength=3)} "
         f"V rows {r.counts[3:6] // 128}")
 
@@ -154,7 +154,7 @@ def test_decode_random_shapes_lengths_and_parameters(T):
         say(f"random case {case}: cfg{cfg} G{G} Hkv{Hkv} B{B} Ncap{Ncap} lens{lens} {params} path{path}")
         gc, oc, out, dbg, r = T.run_both(w.k, w.v, w.q, lens, Ncap=Ncap, path=path, **params)
         T.assert_cache_equal(gc, oc)
-        T.assert_decode_equal(out, dbg, r, lens, G, f"random case {case}")
+        T.assert_decode_equal(out, dbg, r, lens, G, f"random case {case}", scale=params.get("scale", 0.0))
         # one more token where there is room, appended and attended to in one call
         room = [n < Ncap for n in lens]
         if any(room):
@@ -166,7 +166,7 @@ def test_decode_random_shapes_lengths_and_parameters(T):
             torch.cuda.synchronize()
             r2 = O.decode_attention(oc, T.bits(w.q), **params)
             T.assert_cache_equal(gc, oc)
-            T.assert_decode_equal(out2, dbg, r2, oc.lens.tolist(), G, f"random case {case} + 1 token")
+            T.assert_decode_equal(out2, dbg, r2, oc.lens.tolist(), G, f"random case {case} + 1 token", scale=params.get("scale", 0.0))
 
 
 @pytest.mark.parametrize("B,Hkv,G", [(3, 7, 1), (5, 5, 2), (9, 2, 4)])
@@ -276,21 +276,46 @@ def test_max_len_hint_gives_the_same_result(T):
         assert torch.equal(o1, o2)
 
 
-def test_max_len_hint_below_a_length_leaves_the_library_in_order(T):
-    """A hint below a sequence's length is a caller's mistake; the token-split kernels then leave the tokens past it
-    out, and the next correct call must not see anything stale (tickets, partial results)."""
+def test_max_len_hint_below_a_length_attends_the_first_max_len_tokens_on_both_paths(T):
+    """A bound below a sequence's length: both paths attend to the first max_len tokens of that sequence (the oracle on
+    the truncated lengths), count the sequence in flags[AKV_FLAG_MAXLEN], and leave nothing stale for the next call.
+    With an append in the same call the bound is on the lengths after the append: one too small leaves the new token
+    out of the attention (it is stored all the same)."""
     from paper_2409_16546_amd import workloads, binding as A
-    say("decode: max_len below a length, then a correct call (split path, adaptive and fp16)")
+    from oracle import akv_oracle as O
+    say("decode: max_len below a length, both paths, then a correct call; fp16 kernels the same")
     w = workloads.make(2, B=2, Hq=4, Hkv=2, N=3000)
     lens = [3000, 1500]
-    gc = T.gpu_cache(w.k, w.v, lens, w.Hq, 4096)
     q = w.q.to(DEV)
-    ref = A.akv_decode_attention(gc, q, path=2).clone()
-    short = A.akv_decode_attention(gc, q, max_len=1100, path=2).clone()
-    again = A.akv_decode_attention(gc, q, path=2).clone()
-    torch.cuda.synchronize()
-    assert torch.isfinite(short.float()).all()
-    assert torch.equal(ref, again)
+    oc_cut = T.oracle_cache(w.k, w.v, lens, 4096)
+    oc_cut.lens[:] = 1100                  # K_colmax stays the running maximum over everything that was stored
+    r_cut = O.decode_attention(oc_cut, T.bits(w.q))
+    for path in (1, 2):
+        gc = T.gpu_cache(w.k, w.v, lens, w.Hq, 4096)
+        ref = A.akv_decode_attention(gc, q, path=path).clone()
+        dbg = A.DebugBuffers.allocate(gc)
+        short = A.akv_decode_attention(gc, q, max_len=1100, path=path, dbg=dbg).clone()
+        again = A.akv_decode_attention(gc, q, path=path).clone()
+        torch.cuda.synchronize()
+        T.assert_decode_equal(short, dbg, r_cut, [1100, 1100], 2, f"max_len 1100 path {path}")
+        assert torch.equal(ref, again)
+        assert int(gc.flags.cpu()[A.AKV_FLAG_MAXLEN]) == 2          # both sequences exceeded the bound, one call
+        # append + decode with the bound of the lengths BEFORE the append: the new token is stored, not attended
+        gen = torch.Generator().manual_seed(3)
+        kn = torch.randn(2, 2, 1, 128, generator=gen).half()
+        vn = torch.randn(2, 2, 1, 128, generator=gen).half()
+        gc2 = T.gpu_cache(w.k[:, :, :1100], w.v[:, :, :1100], [1100, 1100], w.Hq, 4096)
+        dbg2 = A.DebugBuffers.allocate(gc2)
+        out2 = A.akv_append_decode_attention(gc2, kn.to(DEV), vn.to(DEV), q, max_len=1100, path=path, dbg=dbg2)
+        torch.cuda.synchronize()
+        oc2 = T.oracle_cache(w.k[:, :, :1100], w.v[:, :, :1100], [1100, 1100], 4096)
+        O.append(oc2, T.bits(kn), T.bits(vn))
+        T.assert_cache_equal(gc2, oc2)
+        assert gc2.lens.cpu().tolist() == [1101, 1101] and int(gc2.flags.cpu()[A.AKV_FLAG_MAXLEN]) == 2
+        oc2.lens[:] = 1100                 # attended: the first 1100 tokens, K_colmax counting the new token
+        r2 = O.decode_attention(oc2, T.bits(w.q))
+        T.assert_decode_equal(out2, dbg2, r2, [1100, 1100], 2, f"append with max_len of before, path {path}")
+    gc = T.gpu_cache(w.k, w.v, lens, w.Hq, 4096)
     ku, vu = A.akv_unpack(gc)
     lens_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
     f_ref = A.akv_fp16_decode_attention(ku, vu, lens_d, q).clone()
@@ -413,79 +438,49 @@ def test_append_decode_in_one_call_across_block_chunk_and_prefetch_boundaries(T,
         assert torch.equal(gc2_out, out)
 
 
-def test_cfg2_full_size_sampled_against_oracle(T):
-    """Benchmark configuration 2 at full size in the launch configuration bench.py times (max_len = N, no debug
-    exports in the timed call); 6 sampled (sequence, head) pairs are recomputed by the oracle."""
-    from paper_2409_16546_amd import workloads, binding as A
-    from oracle import akv_oracle as O
-    say("full size: cfg2 B8 H32/32 N4096, 6 sampled (b, h) pairs")
-    w = workloads.make(2)
-    N = 4096
-    gc = T.gpu_cache(w.k, w.v, w.lens.tolist(), w.Hq, N)
-    q = w.q.to(DEV)
-    out_plain = A.akv_decode_attention(gc, q, max_len=N).clone()       # the benchmarked launch (library's choice of path)
-    dbg = A.DebugBuffers.allocate(gc)
-    out_dbg = A.akv_decode_attention(gc, q, max_len=N, dbg=dbg)
-    out_split = A.akv_decode_attention(gc, q, max_len=N, path=2)       # the other path, same masks
-    torch.cuda.synchronize()
-    assert torch.equal(out_plain, out_dbg)                              # exports do not change the result
-    assert (out_plain - out_split).abs().max().item() <= 1e-4          # summation order differs between the paths
-    rng = np.random.default_rng(0)
-    for b, h in zip(rng.integers(0, 8, 6), rng.integers(0, 32, 6)):
-        b, h = int(b), int(h)
-        oc = T.oracle_cache(w.k[b:b + 1, h:h + 1], w.v[b:b + 1, h:h + 1], [N], N)
-        r = O.decode_attention(oc, T.bits(w.q[b:b + 1, h:h + 1]))
-        sub = A.DebugBuffers(dbg.lvlK[b:b + 1, h:h + 1], dbg.logits[b:b + 1, h:h + 1], dbg.a[b:b + 1, h:h + 1],
-                             dbg.sel[b:b + 1, h:h + 1], dbg.oest[b:b + 1, h:h + 1], dbg.Ehat[b:b + 1, h:h + 1],
-                             dbg.needV[b:b + 1, h:h + 1], dbg.appliedV[b:b + 1, h:h + 1])
-        sub = A.DebugBuffers(*[x.contiguous() if x is not None else None for x in
-                               (sub.lvlK, sub.logits, sub.a, sub.sel, sub.oest, sub.Ehat, sub.needV, sub.appliedV)])
-        err, rl2 = T.assert_decode_equal(out_plain[b:b + 1, h:h + 1], sub, r, [N], 1, f"cfg2 b={b} h={h}")
-        say(f"  b={b} h={h}: max-abs {err:.2e} rel-L2 {rl2:.2e}")
-
-
-@pytest.mark.parametrize("cfg,path", [(3, 0), (3, 1), (4, 0), (5, 0)], ids=["cfg3", "cfg3-head-path", "cfg4", "cfg5"])
-def test_full_size_configs_3_to_5_sampled_against_oracle(T, cfg, path):
-    """Benchmark configurations 3-5 at full size.  With the library's choice of path all three run the token-split
-    kernels (config 3: B16, MHA, 8192 tokens, the last token appended inside the step -- two rounds of pairs;
-    configs 4 and 5: GQA 32/8, 32768 tokens / ragged lengths up to 131072).  Config 3 is also run on the
-    head-per-workgroup kernel (fused append, two blocks per wave, two chunks in the mid step).  Three sampled
-    (sequence, KV head) pairs are recomputed by the oracle."""
+@pytest.mark.parametrize("cfg,path", [(1, 0), (2, 0), (3, 0), (3, 1), (4, 0), (5, 0)],
+                         ids=["cfg1", "cfg2", "cfg3", "cfg3-head-path", "cfg4", "cfg5"])
+def test_full_size_configurations_against_the_oracle_everywhere(T, cfg, path):
+    """The five benchmark configurations at full size, in the launch configuration the benchmark times (max_len = the
+    longest sequence, the library's choice of path, no exports in the timed call; config 3 with its last token appended
+    inside the step, and also on the head-per-workgroup kernel: fused append, two blocks per wave).  The oracle runs the
+    WHOLE configuration: every plane byte, every lvlK, logit, score exponent, selection, O_est, result exponent, needV
+    and appliedV of every (sequence, head) is compared bit for bit, every output within the tolerance, and the device
+    counters with the oracle's counts."""
     from paper_2409_16546_amd import workloads, binding as A
     from oracle import akv_oracle as O
     w = workloads.make(cfg)
     G, N = w.Hq // w.Hkv, w.Ncap
     lens = w.lens.tolist()
-    say(f"full size: cfg{cfg} B{w.B} H{w.Hq}/{w.Hkv} Ncap{N} lens {lens[:4]}...")
+    say(f"full size: cfg{cfg} B{w.B} H{w.Hq}/{w.Hkv} Ncap{N} lens {lens[:4]}... path {path}")
     q = w.q.to(DEV)
-    dbg = None
+    stats = A.new_stats(DEV)
     if w.append_last:
         before = [n - 1 for n in lens]
         gc = T.gpu_cache(w.k, w.v, before, w.Hq, N)
         kn = torch.stack([w.k[b, :, lens[b] - 1:lens[b]] for b in range(w.B)]).contiguous()
         vn = torch.stack([w.v[b, :, lens[b] - 1:lens[b]] for b in range(w.B)]).contiguous()
         dbg = A.DebugBuffers.allocate(gc)
-        out = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), q, max_len=max(lens), dbg=dbg, path=path)
+        out = A.akv_append_decode_attention(gc, kn.to(DEV), vn.to(DEV), q, max_len=max(lens), dbg=dbg, path=path, stats=stats)
     else:
         gc = T.gpu_cache(w.k, w.v, lens, w.Hq, N)
         dbg = A.DebugBuffers.allocate(gc)
-        out = A.akv_decode_attention(gc, q, max_len=max(lens), dbg=dbg, path=path)
+        out = A.akv_decode_attention(gc, q, max_len=max(lens), dbg=dbg, path=path, stats=stats)
     plain = A.akv_decode_attention(gc, q, max_len=max(lens), path=path)           # the launch without exports
     torch.cuda.synchronize()
-    assert torch.equal(plain, out)
-    assert gc.lens.cpu().tolist() == lens
-    rng = np.random.default_rng(cfg)
-    for b, h in zip(rng.integers(0, w.B, 3), rng.integers(0, w.Hkv, 3)):
-        b, h = int(b), int(h)
-        n = lens[b]
-        hs = slice(h * G, (h + 1) * G)
-        oc = T.oracle_cache(w.k[b:b + 1, h:h + 1, :n], w.v[b:b + 1, h:h + 1, :n], [n], N)
-        r = O.decode_attention(oc, T.bits(w.q[b:b + 1, hs]))
-        for name in ("k_hi", "k_mid", "k_lo", "v_hi", "v_mid", "v_lo"):   # the planes of this pair, byte for byte
-            plane = getattr(gc, name).view(w.B, w.Hkv, -1)[b, h].cpu().numpy()
-            assert np.array_equal(plane, getattr(oc, name).reshape(-1)), f"cfg{cfg} b={b} h={h}: plane {name} differs"
-        sub = A.DebugBuffers(*[x.contiguous() for x in (
-            dbg.lvlK[b:b + 1, h:h + 1], dbg.logits[b:b + 1, hs], dbg.a[b:b + 1, hs], dbg.sel[b:b + 1, hs],
-            dbg.oest[b:b + 1, hs], dbg.Ehat[b:b + 1, h:h + 1], dbg.needV[b:b + 1, h:h + 1], dbg.appliedV[b:b + 1, h:h + 1])])
-        err, rl2 = T.assert_decode_equal(out[b:b + 1, hs], sub, r, [n], G, f"cfg{cfg} b={b} h={h}")
-        say(f"  b={b} h={h} len={n}: max-abs {err:.2e} rel-L2 {rl2:.2e}")
+    assert torch.equal(plain, out)                                                  # exports do not change the result
+    assert gc.lens.cpu().tolist() == lens and not gc.flags.cpu()[:A.AKV_NFLAGS].any()
+    say("  GPU done; oracle on the whole configuration ...")
+    oc = T.oracle_cache(w.k, w.v, lens, N)
+    r = O.decode_attention(oc, T.bits(w.q))
+    say("  oracle done; comparing")
+    T.assert_cache_equal(gc, oc)
+    err, rl2 = T.assert_decode_equal(out, dbg, r, lens, G, f"cfg{cfg}")
+    T.assert_stats_equal(stats, r, f"cfg{cfg}")
+    bits_k = (8 * r.counts[0] + 12 * r.counts[1] + 16 * r.counts[2]) / r.counts[0:3].sum()
+    bits_v = (8 * r.counts[3] + 12 * r.counts[4] + 16 * r.counts[5]) / r.counts[3:6].sum()
+    say(f"  cfg{cfg}: max-abs {err:.2e} rel-L2 {rl2:.2e}; bits read per element K {bits_k:.2f} V {bits_v:.2f}")
+    if cfg == 2:   # the other path gives the same masks; its sums run in another order
+        out_other = A.akv_decode_attention(gc, q, max_len=max(lens), path=2)
+        torch.cuda.synchronize()
+        assert (plain - out_other).abs().max().item() <= 1e-4

@@ -204,6 +204,21 @@ akv_status akv_decode_attention(const akv_cache *cache, const uint16_t *q, void 
                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * akv_decode_attention for callers that cannot allocate device memory or keep a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments and results as
+ * akv_decode_attention, but the scratch memory is a file-scope device array of AKV_STATIC_SCRATCH_BYTES inside the
+ * library (one copy per GPU, held until the process ends); the call allocates and frees nothing.  A shape whose
+ * workspace (akv_sizes.workspace + 64 KiB) exceeds that size, or with B * Hkv > 8192, is refused with
+ * AKV_EWORKSPACE and a text that names both sizes.  Every call on a GPU shares that GPU's array: calls that
+ * overlap on one GPU (two streams, two threads) race; order them on one stream.  The control words the kernels
+ * rely on lie at a fixed place at the front of the array, are zeroed by a fill kernel on the first call on each
+ * device and are left at zero by every call, so a call may follow one of any other shape.
+ */
+#define AKV_STATIC_SCRATCH_BYTES (48u << 20)
+akv_status akv_decode_attention_static(const akv_cache *cache, const uint16_t *q, void *out, const akv_params *params,
+                                       void *stream);
+
+/*
  * One decode step in one call: append one token per sequence (k_new, v_new:
  * device fp16 [B][Hkv][D], as akv_append with n = 1 and n_new = NULL), then
  * akv_decode_attention over the cache including that token.  Same results as

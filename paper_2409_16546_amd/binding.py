@@ -20,8 +20,9 @@ AKV_TB = 256
 AKV_NFLAGS = 4
 AKV_FLAG_OVERFLOW, AKV_FLAG_MAXLEN = 0, 1
 AKV_MAX_TOPK = 64
+AKV_STATIC_SCRATCH_BYTES = 48 << 20
 EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
-           "akv_decode_attention", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read",
+           "akv_decode_attention", "akv_decode_attention_static", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read",
            "akw_layout_sizes", "akw_workspace_init", "akw_pack", "akw_unpack", "akw_gemv"]
 AKW_MAX_B = 4
 
@@ -96,6 +97,8 @@ def lib() -> C.CDLL:
         L.akv_decode_attention.restype = C.c_int
         L.akv_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.POINTER(akv_params), C.c_void_p,
                                            C.c_size_t, C.c_void_p]
+        L.akv_decode_attention_static.restype = C.c_int
+        L.akv_decode_attention_static.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.POINTER(akv_params), C.c_void_p]
         L.akv_append_decode_attention.restype = C.c_int
         L.akv_append_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                   C.POINTER(akv_params), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -280,6 +283,21 @@ def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None
     p = _params(out, scale, topk, guard_bits, force_level, max_len, d, events, path, stats)
     s = cache.struct()
     _check(lib().akv_decode_attention(C.byref(s), _ptr(q), _ptr(out), C.byref(p), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def akv_decode_attention_static(cache: Cache, q: torch.Tensor, out: torch.Tensor, *, scale: float = 0.0,
+                                topk: int = 32, guard_bits: int = 0, force_level: int = -1, max_len: int = 0,
+                                dbg: DebugBuffers | None = None, events=None, path: int = 0,
+                                stats: torch.Tensor | None = None) -> torch.Tensor:
+    """akv_decode_attention on the library's own static scratch array: the call allocates nothing (out is the
+    caller's); shapes beyond AKV_STATIC_SCRATCH_BYTES are refused."""
+    assert q.dtype == torch.float16 and tuple(q.shape) == (cache.B, cache.Hq, cache.D)
+    assert out.dtype in (torch.float32, torch.float16) and tuple(out.shape) == tuple(q.shape)
+    d = dbg.struct() if dbg is not None else None
+    p = _params(out, scale, topk, guard_bits, force_level, max_len, d, events, path, stats)
+    s = cache.struct()
+    _check(lib().akv_decode_attention_static(C.byref(s), _ptr(q), _ptr(out), C.byref(p), _stream()))
     return out
 
 

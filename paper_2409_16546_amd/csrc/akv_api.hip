@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "akv_common.h"
 
@@ -150,9 +151,36 @@ akv_status akv_unpack(const akv_cache* cache, uint16_t* k_out, uint16_t* v_out, 
 
 }  // extern "C"
 
+// ---- the scratch of akv_decode_attention_static: one device array per GPU, never allocated or freed ------------
+// In host code the array's name is only a handle: its device address is looked up per device and kept.
+static __device__ __align__(256) unsigned char akv_static_scratch[AKV_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using akv::compute_units;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the static scratch array on the current device; on the first call on a device its control block
+// is zeroed by a fill kernel on `s` (ordered in front of the decode kernels that follow on the same stream).
+// Returns nullptr after recording the error text.
+void* static_scratch_for_current_device(hipStream_t s)
+{
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev)) { hip_fail(e, "hipGetDevice"); return nullptr; }
+    if (dev < 0 || dev >= kMaxDevices) { fail(AKV_EHIP, "device ordinal %d out of range", dev); return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(akv_static_scratch))) { hip_fail(e, "hipGetSymbolAddress"); return nullptr; }
+        if (!ptr) { fail(AKV_EHIP, "hipGetSymbolAddress returned a null address"); return nullptr; }
+        if (hipError_t e = akv::launch_zero(ptr, akv::kCtlReserve, s)) { hip_fail(e, "zero launch"); return nullptr; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 // Head-per-workgroup or token-split kernels, when the caller leaves the choice to the library.  One head kernel
 // workgroup occupies a compute unit, so `pairs` (sequence, KV head) pairs run in ceil(pairs / CUs) rounds of equal
@@ -189,6 +217,16 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
     if (p.max_len < 0 || p.max_len > cache->shape.Ncap) return fail(AKV_EINVAL, "max_len = %d out of range 0..Ncap", p.max_len);
     if (!(p.scale == p.scale) || std::isinf(p.scale)) return fail(AKV_EINVAL, "scale is not finite");
     const akv::WsLayout w = akv::ws_layout(cache->shape, static_scratch);
+    if (static_scratch) {
+        if (w.total > AKV_STATIC_SCRATCH_BYTES || w.control_bytes > akv::kCtlReserve)
+            return fail(AKV_EWORKSPACE, "this shape needs %zu bytes of scratch (%zu of control words); the static array holds %zu (%zu): "
+                        "use akv_decode_attention with a workspace of the caller's", w.total, w.control_bytes,
+                        size_t(AKV_STATIC_SCRATCH_BYTES), akv::kCtlReserve);
+        hipStream_t s0 = static_cast<hipStream_t>(stream);
+        workspace = static_scratch_for_current_device(s0);
+        if (!workspace) return AKV_EHIP;   // the text has been recorded
+        workspace_bytes = AKV_STATIC_SCRATCH_BYTES;
+    }
     if (!workspace || workspace_bytes < w.total)
         return fail(AKV_EWORKSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, w.total);
     if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(AKV_EWORKSPACE, "workspace is not 256-byte aligned");
@@ -267,6 +305,12 @@ akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void*
                                 void* workspace, size_t workspace_bytes, void* stream)
 {
     return decode_impl(cache, nullptr, nullptr, q, out, params, workspace, workspace_bytes, stream);
+}
+
+akv_status akv_decode_attention_static(const akv_cache* cache, const uint16_t* q, void* out, const akv_params* params,
+                                       void* stream)
+{
+    return decode_impl(cache, nullptr, nullptr, q, out, params, nullptr, 0, stream, true);
 }
 
 akv_status akv_append_decode_attention(const akv_cache* cache, const uint16_t* k_new, const uint16_t* v_new,

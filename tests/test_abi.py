@@ -113,6 +113,23 @@ def test_misaligned_pointers_are_refused_before_anything_is_launched(A):
     refused(L.akv_decode_attention(C.byref(good), q, out, C.byref(p), ws, 1 << 30, None), "stats")
 
 
+def test_static_scratch_entry_point_refuses_shapes_beyond_its_array(A):
+    # host-side check only (made-up addresses): the refusal comes before anything touches the device
+    L = A.lib()
+    planes = {n: 0x10000 * (i + 1) for i, n in enumerate(("k_hi", "k_mid", "k_lo", "v_hi", "v_mid", "v_lo", "colmax",
+                                                           "lens", "flags"))}
+    for shape in ((4, 32, 8, 128, 131072), (1024, 16, 16, 128, 256)):   # too many logits; too many control words
+        sz = A.akv_layout_sizes(*shape)
+        big = A.akv_cache(A.akv_shape(*shape), **planes)
+        assert L.akv_decode_attention_static(C.byref(big), 0x200000, 0x300000, None, None) == A.AKV_EWORKSPACE
+        msg = L.akv_last_error().decode()
+        assert str(A.AKV_STATIC_SCRATCH_BYTES) in msg and "static" in msg
+        assert sz.workspace + 65536 > A.AKV_STATIC_SCRATCH_BYTES or shape[0] * shape[2] > 8192
+    # the header's constant is the binding's
+    text = open(os.path.join(ROOT, "include", "akv.h")).read()
+    assert re.search(r"#define AKV_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1) == str(A.AKV_STATIC_SCRATCH_BYTES >> 20)
+
+
 def test_misaligned_weight_arrays_are_refused(A):
     L = A.lib()
     w = A.akw_weights(64, 32, 0x10000, 0x20000, 0x30000, 0x40000)

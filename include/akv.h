@@ -143,17 +143,19 @@ typedef struct akv_params {
                              longer than max_len is attended over its first max_len tokens only (on either
                              path) and counted in flags[AKV_FLAG_MAXLEN]                               */
     const akv_debug *dbg; /* host pointer to a struct of device pointers, or NULL                    */
-    void *const *events;  /* host pointer to 3 hipEvent_t, or NULL: the library records them on the
-                             stream before its first kernel, in front of the V kernel of
-                             the token-split path (on the head-per-workgroup path, which is one kernel:
-                             right after event 0) and after its last kernel, so that a caller can time
-                             the kernels in place                                                   */
+    void *const *events;  /* host pointer to AKV_NEVENTS hipEvent_t, or NULL: the library records them on the
+                             stream so that a caller can time the kernels in place -- [0] before its first
+                             kernel, [1] in front of the K kernel (after the append kernel where
+                             akv_append_decode_attention runs one), [2] after the K kernel, [3] in front of
+                             the V kernel, [4] after its last kernel.  On the head-per-workgroup path, which
+                             is one kernel, [1], [2] and [3] follow [0] at once                        */
     int32_t path;         /* 0: choose; 1: head-per-workgroup path (one kernel; needs Hq/Hkv <= 4);
                              2: token-split path (four kernels).  Both give the same decisions.       */
     akv_stats *stats;     /* DEVICE pointer to counters the call adds to, or NULL                    */
 } akv_params;
 
 #define AKV_MAX_TOPK 64
+#define AKV_NEVENTS 5
 
 /* Library version (major*100 + minor). */
 int akv_version(void);
@@ -202,6 +204,11 @@ akv_status akv_workspace_init(const akv_shape *shape, void *workspace, size_t wo
  */
 akv_status akv_decode_attention(const akv_cache *cache, const uint16_t *q, void *out, const akv_params *params,
                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Which kernels akv_decode_attention takes for this shape when params->path is 0: 1 = head-per-workgroup (one
+ * kernel), 2 = token-split (four kernels); max_len as in akv_params (0 means Ncap).  Host computation; 0 on a bad
+ * shape.  For callers that attribute time to kernels. */
+int32_t akv_decode_path(const akv_shape *shape, int32_t max_len);
 
 /*
  * akv_decode_attention for callers that cannot allocate device memory or keep a workspace: code under HIP graph

@@ -20,9 +20,10 @@ AKV_TB = 256
 AKV_NFLAGS = 4
 AKV_FLAG_OVERFLOW, AKV_FLAG_MAXLEN = 0, 1
 AKV_MAX_TOPK = 64
+AKV_NEVENTS = 5
 AKV_STATIC_SCRATCH_BYTES = 48 << 20
 EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
-           "akv_decode_attention", "akv_decode_attention_static", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read",
+           "akv_decode_attention", "akv_decode_path", "akv_decode_attention_static", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read",
            "akw_layout_sizes", "akw_workspace_init", "akw_pack", "akw_unpack", "akw_gemv"]
 AKW_MAX_B = 4
 
@@ -97,6 +98,8 @@ def lib() -> C.CDLL:
         L.akv_decode_attention.restype = C.c_int
         L.akv_decode_attention.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.POINTER(akv_params), C.c_void_p,
                                            C.c_size_t, C.c_void_p]
+        L.akv_decode_path.restype = C.c_int32
+        L.akv_decode_path.argtypes = [C.POINTER(akv_shape), C.c_int32]
         L.akv_decode_attention_static.restype = C.c_int
         L.akv_decode_attention_static.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.POINTER(akv_params), C.c_void_p]
         L.akv_append_decode_attention.restype = C.c_int
@@ -254,6 +257,12 @@ class DebugBuffers:
                          _ptr(self.Ehat), _ptr(self.needV), _ptr(self.appliedV))
 
 
+def akv_decode_path(B: int, Hq: int, Hkv: int, D: int, Ncap: int, max_len: int = 0) -> int:
+    """1 (head-per-workgroup kernel) or 2 (token-split kernels): what path=0 takes for this shape."""
+    shp = akv_shape(B, Hq, Hkv, D, Ncap)
+    return int(lib().akv_decode_path(C.byref(shp), max_len))
+
+
 def new_stats(device="cuda:0") -> torch.Tensor:
     """Zeroed device counters for the `stats` argument of the decode calls: int64 [9] = k_elems[3], v_row_elems[3],
     v_need_elems[3] (the fields of akv_stats in order); every call adds to them."""
@@ -272,7 +281,7 @@ def akv_decode_attention(cache: Cache, q: torch.Tensor, out: torch.Tensor | None
                          dbg: DebugBuffers | None = None, workspace: torch.Tensor | None = None,
                          events=None, path: int = 0, stats: torch.Tensor | None = None) -> torch.Tensor:
     """q: fp16 [B, Hq, D] on the device; out: float32 or fp16 [B, Hq, D] (allocated if None).
-    events: None or a ctypes array of 3 hipEvent_t handles the library records around its kernels.
+    events: None or a ctypes array of AKV_NEVENTS hipEvent_t handles the library records around its kernels.
     path: 0 choose, 1 head-per-workgroup kernel, 2 token-split kernels.  stats: see new_stats()."""
     assert q.dtype == torch.float16 and tuple(q.shape) == (cache.B, cache.Hq, cache.D)
     if out is None:

@@ -283,17 +283,20 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
         if (hipError_t e = hipEventRecord(ev(0), s)) return hip_fail(e, "hipEventRecord");
     if (head_path) {
         if (p.events)
-            if (hipError_t e = hipEventRecord(ev(1), s)) return hip_fail(e, "hipEventRecord");
+            for (int i = 1; i < 4; ++i)
+                if (hipError_t e = hipEventRecord(ev(i), s)) return hip_fail(e, "hipEventRecord");
         a.k_new = k_new;   // the head kernel stores the new token itself
         a.v_new = v_new;
         if (hipError_t e = akv::launch_decode_head(a, s)) return hip_fail(e, "decode (head path) launch");
     } else {
         if (k_new)
             if (hipError_t e = akv::launch_append(*cache, k_new, v_new, nullptr, 1, s)) return hip_fail(e, "append launch");
-        if (hipError_t e = akv::launch_decode_split(a, s, ev(1))) return hip_fail(e, "decode (split path) launch");
+        if (p.events)
+            if (hipError_t e = hipEventRecord(ev(1), s)) return hip_fail(e, "hipEventRecord");
+        if (hipError_t e = akv::launch_decode_split(a, s, ev(2), ev(3))) return hip_fail(e, "decode (split path) launch");
     }
     if (p.events)
-        if (hipError_t e = hipEventRecord(ev(2), s)) return hip_fail(e, "hipEventRecord");
+        if (hipError_t e = hipEventRecord(ev(4), s)) return hip_fail(e, "hipEventRecord");
     return AKV_OK;
 }
 
@@ -305,6 +308,13 @@ akv_status akv_decode_attention(const akv_cache* cache, const uint16_t* q, void*
                                 void* workspace, size_t workspace_bytes, void* stream)
 {
     return decode_impl(cache, nullptr, nullptr, q, out, params, workspace, workspace_bytes, stream);
+}
+
+int32_t akv_decode_path(const akv_shape* shape, int32_t max_len)
+{
+    if (!shape || !shape_ok(*shape) || max_len < 0 || max_len > shape->Ncap) return 0;
+    const int ml = max_len > 0 ? max_len : shape->Ncap;
+    return akv::head_path_supported(*shape) && head_path_pays(long(shape->B) * shape->Hkv, shape->Hq / shape->Hkv, ml) ? 1 : 2;
 }
 
 akv_status akv_decode_attention_static(const akv_cache* cache, const uint16_t* q, void* out, const akv_params* params,

@@ -153,7 +153,7 @@ hipError_t launch_append(const akv_cache& c, const uint16_t* k_new, const uint16
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t* sink, hipStream_t st);
 hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, hipStream_t st);
-hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event);   // four kernels; mid_event (may be null) is recorded in front of the last
+hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t k_done_event, hipEvent_t mid_event);   // four kernels; the events (may be null) are recorded after the first and in front of the last
 hipError_t launch_decode_head(const DecodeArgs& a, hipStream_t st);                         // one kernel, a head per workgroup
 bool head_path_supported(const akv_shape& s);
 hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v, const int32_t* lens, const uint16_t* q,

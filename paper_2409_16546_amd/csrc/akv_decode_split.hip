@@ -377,12 +377,14 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 }
 
 template <int G>
-static hipError_t launch_split_g(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event)
+static hipError_t launch_split_g(const DecodeArgs& a, hipStream_t st, hipEvent_t k_done_event, hipEvent_t mid_event)
 {
     const int tile = kTB * kKWaves;   // tokens per workgroup of the K kernel: one 256-token block per wave
     const dim3 kgrid((a.max_len + tile - 1) / tile, a.s.Hkv, a.s.B), kblock(64 * kKWaves);
     hipLaunchKernelGGL((split_k_kernel<G>), kgrid, kblock, 0, st, a);
     if (hipError_t e = hipGetLastError()) return e;
+    if (k_done_event)
+        if (hipError_t e = hipEventRecord(k_done_event, st)) return e;
     hipLaunchKernelGGL((split_slice_kernel<G>), kgrid, dim3(256), 0, st, a);   // one workgroup per slice here as well
     if (hipError_t e = hipGetLastError()) return e;
     hipLaunchKernelGGL((split_select_kernel<G>), dim3(a.s.Hkv, a.s.B), dim3(256), 0, st, a);
@@ -395,13 +397,13 @@ static hipError_t launch_split_g(const DecodeArgs& a, hipStream_t st, hipEvent_t
     return hipGetLastError();
 }
 
-hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t mid_event)
+hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t k_done_event, hipEvent_t mid_event)
 {
     switch (a.s.Hq / a.s.Hkv) {
-        case 1: return launch_split_g<1>(a, st, mid_event);
-        case 2: return launch_split_g<2>(a, st, mid_event);
-        case 4: return launch_split_g<4>(a, st, mid_event);
-        case 8: return launch_split_g<8>(a, st, mid_event);
+        case 1: return launch_split_g<1>(a, st, k_done_event, mid_event);
+        case 2: return launch_split_g<2>(a, st, k_done_event, mid_event);
+        case 4: return launch_split_g<4>(a, st, k_done_event, mid_event);
+        case 8: return launch_split_g<8>(a, st, k_done_event, mid_event);
         default: return hipErrorInvalidValue;
     }
 }

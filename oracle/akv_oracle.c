@@ -498,6 +498,87 @@ int akvo_fp16_attention(int B, int Hq, int Hkv, int D, int Ncap, const uint16_t 
     return 0;
 }
 
+/* ---------- exported: what other fetch granules would read (studies, no kernel reads the cache that way) -------
+ * "Dynamic Quantization" (data re-arrangement): the hardware reads in units of several bytes, so the level that is
+ * applied is the maximum of the per-element needs over a fetch unit.  The cache's unit for V is one token row
+ * (1 token x D channels).  This function answers what a unit of tt tokens x cc channels would read instead.
+ * needV: [B][Hkv][Ncap][D] per-element levels as akvo_decode_attention exports them; tt divides 256, cc divides D.
+ * counts[l] = V elements (of tokens t < lens[b]) that would be read at level l.  Returns 0, or -1 on bad arguments. */
+int akvo_v_granule_counts(int B, int Hkv, int D, int Ncap, const uint8_t *needV, const int32_t *lens, int tt, int cc,
+                          uint64_t counts[3])
+{
+    if (!shape_ok(B, Hkv, Hkv, D, Ncap) || tt < 1 || cc < 1 || AKVO_TB % tt != 0 || D % cc != 0) return -1;
+    counts[0] = counts[1] = counts[2] = 0;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h)
+            for (int t0 = 0; t0 < lens[b]; t0 += tt)
+                for (int d0 = 0; d0 < D; d0 += cc) {
+                    int lvl = 0, ntok = 0;
+                    for (int t = t0; t < t0 + tt && t < lens[b]; ++t) {
+                        ++ntok;
+                        for (int d = d0; d < d0 + cc; ++d) {
+                            int need = needV[((((size_t)b * Hkv + h) * Ncap) + t) * D + d];
+                            if (need > lvl) lvl = need;
+                        }
+                    }
+                    counts[lvl] += (uint64_t)ntok * (uint64_t)cc;
+                }
+    return 0;
+}
+
+/* Rule 1 with one column maximum per `block` tokens instead of one per sequence ("Quantization of K-Cache": the
+ * data within a column are only relatively similar).  For every block of `block` tokens (block a multiple of 1,
+ * blocks start at token 0) the column maxima are taken over the tokens of that block only, and the K rule of
+ * akvo_decode_attention is applied with them: coarsest addend and every addend bounded inside the block.
+ * lvl_out: [B][Hkv][ceil(Ncap / block)][D] levels per (block, column), or NULL; counts[l] = K elements (tokens
+ * t < lens[b]) read at level l.  A block >= the sequence reproduces lvlK of akvo_decode_attention. */
+int akvo_k_levels_per_block(int B, int Hq, int Hkv, int D, int Ncap, const uint8_t *k_hi, const uint8_t *k_mid,
+                            const uint8_t *k_lo, const int32_t *lens, const uint16_t *q, int guard_bits, int block,
+                            uint8_t *lvl_out, uint64_t counts[3])
+{
+    if (!shape_ok(B, Hq, Hkv, D, Ncap) || block < 1) return -1;
+    planes_t p = {B, Hkv, D, Ncap, (uint8_t *)k_hi, (uint8_t *)k_mid, (uint8_t *)k_lo, NULL, NULL, NULL};
+    const int G = Hq / Hkv;
+    const int nblk_cap = (Ncap + block - 1) / block;
+    counts[0] = counts[1] = counts[2] = 0;
+    uint16_t *cm = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)D);
+    uint8_t *lvl = (uint8_t *)malloc((size_t)D);
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h)
+            for (int t0 = 0, bi = 0; t0 < lens[b]; t0 += block, ++bi) {
+                int t1 = t0 + block < lens[b] ? t0 + block : lens[b];
+                for (int d = 0; d < D; ++d) {
+                    cm[d] = 0;
+                    for (int t = t0; t < t1; ++t) {
+                        uint16_t mag = load_k(&p, b, h, t, d) & 0x7FFF;
+                        if (mag > cm[d]) cm[d] = mag;
+                    }
+                    lvl[d] = 0;
+                }
+                for (int g = 0; g < G; ++g) {
+                    const uint16_t *qg = q + ((size_t)b * Hq + (size_t)h * G + g) * D;
+                    int emax = -1;
+                    for (int d = 0; d < D; ++d) {
+                        float P = half_to_float(qg[d]) * half_to_float(colmax_floor(cm[d]));
+                        if (P != 0.0f && float_exp_field(P) > emax) emax = float_exp_field(P);
+                    }
+                    for (int d = 0; d < D; ++d) {
+                        float P = half_to_float(qg[d]) * half_to_float(colmax_floor(cm[d]));
+                        int level = 0;
+                        if (P != 0.0f) level = level_for_mantissa_bits(10 + guard_bits - (emax - float_exp_field(P)));
+                        if (level > lvl[d]) lvl[d] = (uint8_t)level;
+                    }
+                }
+                for (int d = 0; d < D; ++d) {
+                    counts[lvl[d]] += (uint64_t)(t1 - t0);
+                    if (lvl_out) lvl_out[((((size_t)b * Hkv + h) * nblk_cap) + bi) * D + d] = lvl[d];
+                }
+            }
+    free(cm);
+    free(lvl);
+    return 0;
+}
+
 int akvo_max_threads(void)
 {
 #ifdef _OPENMP

@@ -56,6 +56,10 @@ def lib():
                                                + [C.c_void_p, C.POINTER(_Debug)])
         _lib.akvo_fp16_attention.restype = C.c_int
         _lib.akvo_fp16_attention.argtypes = [C.c_int] * 5 + [C.c_void_p] * 4 + [C.c_float, C.c_void_p]
+        _lib.akvo_v_granule_counts.restype = C.c_int
+        _lib.akvo_v_granule_counts.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        _lib.akvo_k_levels_per_block.restype = C.c_int
+        _lib.akvo_k_levels_per_block.argtypes = [C.c_int] * 5 + [C.c_void_p] * 5 + [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         _lib.akvo_max_threads.restype = C.c_int
         _lib.akvo_set_threads.restype = None
         _lib.akvo_set_threads.argtypes = [C.c_int]
@@ -176,6 +180,30 @@ def fp16_attention(k: np.ndarray, v: np.ndarray, lens: np.ndarray, q: np.ndarray
     if r != 0:
         raise ValueError("akvo_fp16_attention: bad arguments")
     return out
+
+
+def v_granule_counts(cache: Cache, needV: np.ndarray, tt: int, cc: int) -> np.ndarray:
+    """V elements read at level 0 / 1 / 2 if the fetch unit were tt tokens x cc channels (uint64 [3])."""
+    _chk(needV, np.uint8, (cache.B, cache.Hkv, cache.Ncap, cache.D))
+    counts = np.zeros(3, np.uint64)
+    r = lib().akvo_v_granule_counts(cache.B, cache.Hkv, cache.D, cache.Ncap, _p(needV), _p(cache.lens), tt, cc, _p(counts))
+    if r != 0:
+        raise ValueError("akvo_v_granule_counts: bad arguments")
+    return counts
+
+
+def k_levels_per_block(cache: Cache, q: np.ndarray, block: int, guard_bits: int = 0):
+    """Rule 1 with one column maximum per `block` tokens: (levels uint8 [B, Hkv, ceil(Ncap/block), D], counts uint64 [3])."""
+    B, Hq, D = q.shape
+    _chk(q, np.uint16, (cache.B, Hq, cache.D))
+    nb = (cache.Ncap + block - 1) // block
+    lvl = np.zeros((B, cache.Hkv, nb, D), np.uint8)
+    counts = np.zeros(3, np.uint64)
+    r = lib().akvo_k_levels_per_block(B, Hq, cache.Hkv, D, cache.Ncap, _p(cache.k_hi), _p(cache.k_mid), _p(cache.k_lo),
+                                      _p(cache.lens), _p(q), guard_bits, block, _p(lvl), _p(counts))
+    if r != 0:
+        raise ValueError("akvo_k_levels_per_block: bad arguments")
+    return lvl, counts
 
 
 def max_threads() -> int:

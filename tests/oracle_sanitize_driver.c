@@ -32,6 +32,11 @@ int akvo_decode_attention(int B, int Hq, int Hkv, int D, int Ncap, const uint8_t
                           int guard_bits, int force_level, double *out, const akvo_debug *dbg_in);
 int akvo_fp16_attention(int B, int Hq, int Hkv, int D, int Ncap, const uint16_t *k, const uint16_t *v,
                         const int32_t *lens, const uint16_t *q, float scale, double *out);
+int akvo_v_granule_counts(int B, int Hkv, int D, int Ncap, const uint8_t *needV, const int32_t *lens, int tt, int cc,
+                          uint64_t counts[3]);
+int akvo_k_levels_per_block(int B, int Hq, int Hkv, int D, int Ncap, const uint8_t *k_hi, const uint8_t *k_mid,
+                            const uint8_t *k_lo, const int32_t *lens, const uint16_t *q, int guard_bits, int block,
+                            uint8_t *lvl_out, uint64_t counts[3]);
 double akvo_half_to_double(uint16_t h);
 uint16_t akvo_read_at_level(uint16_t h, int level);
 int akvo_level_for_mantissa_bits(int m);
@@ -142,6 +147,18 @@ static void kv_case(int B, int Hq, int Hkv, int Ncap, const int *len_list, int t
                                 guard, force, out, &dbg) == 0);
     CHECK(akvo_decode_attention(B, Hq, Hkv, D, Ncap, k_hi, k_mid, k_lo, v_hi, v_mid, v_lo, colmax, lens, q, 0.25f, topk,
                                 guard, force, out, NULL) == 0);
+    {   /* the granule studies on the exported needs and on the K planes */
+        uint64_t gc[3];
+        CHECK(akvo_v_granule_counts(B, Hkv, D, Ncap, dbg.needV, lens, 1, D, gc) == 0);
+        CHECK(akvo_v_granule_counts(B, Hkv, D, Ncap, dbg.needV, lens, 4, 32, gc) == 0);
+        CHECK(akvo_v_granule_counts(B, Hkv, D, Ncap, dbg.needV, lens, 256, 1, gc) == 0);
+        CHECK(akvo_v_granule_counts(B, Hkv, D, Ncap, dbg.needV, lens, 3, 32, gc) == -1);
+        const int block = 64, nb = (Ncap + block - 1) / block;
+        uint8_t *lv = exact(bh * (size_t)nb * D);
+        CHECK(akvo_k_levels_per_block(B, Hq, Hkv, D, Ncap, k_hi, k_mid, k_lo, lens, q, guard, block, lv, gc) == 0);
+        CHECK(akvo_k_levels_per_block(B, Hq, Hkv, D, Ncap, k_hi, k_mid, k_lo, lens, q, guard, Ncap, NULL, gc) == 0);
+        free(lv);
+    }
     uint16_t *k_out = exact(bh * (size_t)Ncap * D * 2), *v_out = exact(bh * (size_t)Ncap * D * 2);
     CHECK(akvo_unpack(B, Hkv, D, Ncap, k_hi, k_mid, k_lo, v_hi, v_mid, v_lo, k_out, v_out) == 0);
     CHECK(akvo_fp16_attention(B, Hq, Hkv, D, Ncap, k_out, v_out, lens, q, 0.0f, out) == 0);

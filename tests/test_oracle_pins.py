@@ -565,6 +565,87 @@ def test_out_is_attention_over_the_values_as_they_were_read(oracle, G, force):
         assert np.abs(wrongK - ref).max() > 1e-7 and np.abs(wrongV - ref).max() > 1e-7
 
 
+# ----------------------------------------------------------------------------------------------
+# other fetch granules (studies): "Dynamic Quantization", data re-arrangement -- the hardware reads in units
+# ----------------------------------------------------------------------------------------------
+
+def test_v_granule_counts_against_numpy_block_maxima(oracle):
+    rng = np.random.default_rng(120)
+    B, Hkv, G, N, D = 2, 2, 2, 512, 128
+    q = (rng.normal(size=(B, Hkv * G, D)) * 0.3).astype(np.float16)
+    k = rng.normal(size=(B, Hkv, N, D)).astype(np.float16)
+    v = ((rng.normal(size=(B, Hkv, N, D)) + 1.0) * np.exp2(rng.integers(-8, 1, size=(B, Hkv, N, 1)))
+         * np.exp2(rng.integers(-3, 4, size=(B, Hkv, 1, D)))).astype(np.float16)
+    lens = np.array([512, 333], np.int32)                                   # a ragged sequence: the last unit is partly valid
+    c = fill_cache(oracle, f16bits(k), f16bits(v), lens=lens)
+    r = oracle.decode_attention(c, f16bits(q))
+    assert len(set(r.needV[0, 0, :512].ravel().tolist())) == 3              # every level occurs
+    # the cache's own unit (a token row) and the per-element need are the two counts the decode call reports
+    assert np.array_equal(oracle.v_granule_counts(c, r.needV, 1, D), r.counts[3:6])
+    assert np.array_equal(oracle.v_granule_counts(c, r.needV, 1, 1), r.counts[6:9])
+    bits = lambda cnt: float(8 * cnt[0] + 12 * cnt[1] + 16 * cnt[2]) / float(cnt.sum())
+    for tt, cc in ((2, 128), (2, 64), (4, 32), (8, 16), (1, 64), (1, 32), (16, 128), (256, 128)):
+        got = oracle.v_granule_counts(c, r.needV, tt, cc)
+        want = np.zeros(3, np.uint64)
+        for b in range(B):
+            n = int(lens[b])
+            need = r.needV[b].copy()
+            need[:, n:] = 0                                                  # slots past the sequence ask for nothing
+            ntok = (np.arange(c.Ncap) < n).reshape(c.Ncap // tt, tt).sum(axis=1)            # valid tokens per unit
+            unit = need.reshape(Hkv, c.Ncap // tt, tt, D // cc, cc).max(axis=(2, 4))         # [Hkv, units, channel groups]
+            for lvl in range(3):
+                want[lvl] += np.uint64(((unit == lvl) * ntok[None, :, None]).sum() * cc)
+        assert np.array_equal(got, want), (tt, cc)
+        assert got.sum() == r.counts[3:6].sum()
+        assert bits(got) >= bits(r.counts[6:9])                              # no unit reads less than the elements need
+    # a unit made of whole smaller units never reads less than they do
+    chain = [(1, 32), (1, 64), (1, 128), (2, 128), (4, 128), (16, 128)]
+    b_ = [bits(oracle.v_granule_counts(c, r.needV, tt, cc)) for tt, cc in chain]
+    assert all(x <= y for x, y in zip(b_, b_[1:]))
+    with pytest.raises(ValueError):
+        oracle.v_granule_counts(c, r.needV, 3, 128)
+
+
+@pytest.mark.parametrize("guard", [0, 2])
+def test_k_levels_per_block_against_a_frexp_rewrite_and_the_promised_bound(oracle, guard):
+    rng = np.random.default_rng(130 + guard)
+    G, N, D = 2, 700, 128
+    q, k, v = tiny_case(rng, G, N, D, spread=4)
+    k[0, 0, 100:140, :16] *= np.float16(16.0)                                # a stretch where 16 columns are large: its blocks decide differently
+    k = k.astype(np.float16)
+    c = fill_cache(oracle, f16bits(k), f16bits(v))
+    r = oracle.decode_attention(c, f16bits(q), guard_bits=guard)
+    # one block over the whole sequence is the rule of the decode call
+    lvl, cnt = oracle.k_levels_per_block(c, f16bits(q), c.Ncap, guard)
+    assert np.array_equal(lvl[0, 0, 0], r.lvlK[0, 0]) and np.array_equal(cnt, r.counts[0:3])
+    for block in (64, 256):
+        lvl, cnt = oracle.k_levels_per_block(c, f16bits(q), block, guard)
+        exact = q[0].astype(np.float64) @ k[0, 0].astype(np.float64).T       # [G, N]
+        want_cnt = np.zeros(3, np.uint64)
+        for bi, t0 in enumerate(range(0, N, block)):
+            t1 = min(N, t0 + block)
+            cm = np.maximum(np.abs(k[0, 0, t0:t1]).max(axis=0).astype(np.float64), 2.0 ** -14)
+            want = np.zeros(D, np.int64)
+            emaxs = []
+            for g in range(G):
+                P = np.abs(q[0, g].astype(np.float64)) * cm
+                es = np.array([exp2floor(x) if x != 0 else -10 ** 6 for x in P])
+                emax = es.max()
+                emaxs.append(emax)
+                m = 10 + guard - (emax - es)
+                want = np.maximum(want, np.where(P != 0, (m > 2).astype(np.int64) + (m > 6), 0))
+            assert np.array_equal(lvl[0, 0, bi], want), (block, bi)
+            for lv_ in range(3):
+                want_cnt[lv_] += np.uint64((want == lv_).sum() * (t1 - t0))
+            # the block's own promise: every addend reaches the last place of the block's coarsest addend
+            kt = read_bits_np(f16bits(k)[0, 0, t0:t1], want[None, :])
+            for g in range(G):
+                err = np.abs(kt @ q[0, g].astype(np.float64) - exact[g, t0:t1])
+                assert np.all(err <= int((want < 2).sum()) * 2.0 ** (emaxs[g] - 10 - guard))
+        assert np.array_equal(cnt, want_cnt)
+        assert block == 256 or lvl[0, 0, 1].tolist() != lvl[0, 0, 5].tolist()   # the large stretch changes its block's levels
+
+
 def test_counts_add_up(oracle):
     rng = np.random.default_rng(90)
     q, k, v = tiny_case(rng, 2, 100, 128, spread=3)

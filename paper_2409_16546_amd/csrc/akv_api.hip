@@ -185,14 +185,19 @@ void* static_scratch_for_current_device(hipStream_t s)
 // Head-per-workgroup or token-split kernels, when the caller leaves the choice to the library.  One head kernel
 // workgroup occupies a compute unit, so `pairs` (sequence, KV head) pairs run in ceil(pairs / CUs) rounds of equal
 // length: the path pays when there is one round and it is nearly full, or when the sequences are so short that the
-// single launch outweighs idle units.  The thresholds are where the two paths crossed when timed over pairs =
-// 32..1024, lengths 1024..16384 and group sizes 1, 2, 4 on MI355X.
+// single launch outweighs idle units; for single query heads also at two nearly full rounds, as long as the logits of
+// a pair fit its LDS (the token-split kernels write theirs to memory, and written bytes cost several times what read
+// bytes cost).  The thresholds are where the two paths crossed when timed over pairs = 64..1024, lengths 1024..12288
+// and group sizes 1, 2, 4 on MI355X.
 bool head_path_pays(long pairs, int G, int max_len)
 {
     const long cus = compute_units();
-    if (pairs > cus) return false;
+    if (pairs > cus) return G == 1 && pairs <= 2 * cus && double(pairs) / double(2 * cus) >= 0.85 && max_len <= 8192;
     if (max_len <= (G == 1 ? 2048 : 1024)) return true;
-    return max_len <= 8192 && double(pairs) / double(cus) >= (G == 2 ? 0.9 : 0.72);
+    const double fill = double(pairs) / double(cus);
+    if (G == 1) return (max_len <= 8192 && fill >= 0.72) || (max_len <= 12288 && fill >= 0.85);
+    if (G == 2) return max_len <= 8192 && fill >= 0.9;
+    return (max_len <= 4096 && fill >= 0.72) || (max_len <= 8192 && fill >= 0.95);
 }
 
 // decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])

@@ -9,6 +9,8 @@
 #include "akv_mid_step.h"
 #include "akv_v_rows.h"
 
+#include <algorithm>
+
 namespace akv {
 
 // lens[b] is shared by the heads of a sequence.  Every workgroup reads it at its start and takes a ticket
@@ -31,10 +33,16 @@ template <int G> constexpr int head_v_pre() { return G == 1 ? 3 : 2; }
 // groups of 8 rows per batch of the V side: what the register budget of the launch shape allows
 template <int G, int NT> constexpr int head_v_groups() { return NT <= 512 && G <= 2 ? 4 : 2; }
 
-template <int G, int NT, bool DEBUG>
-__global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
+// LDSLG: the logits of the pair stay in LDS (lds_tokens floats per query head, dynamic shared memory) between the K
+// side, the mid step and the V side instead of going through the workspace: nothing of them is written to memory
+// (16 MB of logits written during a 0.8 GB stream cost as much time as 100 MB of reads on this machine).
+extern __shared__ __align__(16) float head_lds_logits[];
+
+template <int G, int NT, bool DEBUG, bool LDSLG>
+__global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a, int lds_tokens)
 {
     constexpr int kWaves = NT / 64;
+    float* const lds_lg = LDSLG ? head_lds_logits : nullptr;
     __shared__ KShared<G> ks;
     __shared__ MidShared ms;
     __shared__ float wmax_s[G][kWaves];
@@ -119,15 +127,15 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     uint8_t* stage = &kstage[wave_u][0];
     if (pre_any) {   // the block whose first HI bytes are already in flight
         float tm[G];
-        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_k, ks, 0, tm, kpre, true, own, stage);
-        else k_tile<G, true>(a, b, h, blk, len_k, ks, 0, tm, kpre, true, own, stage);
+        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_k, ks, 0, tm, kpre, true, own, stage, lds_lg, lds_tokens);
+        else k_tile<G, true>(a, b, h, blk, len_k, ks, 0, tm, kpre, true, own, stage, lds_lg, lds_tokens);
         blk += 1;
         fold(tm);
     }
     while (blk < blk_end) {
         float tm[G], later[G][4];
-        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_k, ks, 0, tm, kpre, false, later, stage);
-        else k_tile<G, true>(a, b, h, blk, len_k, ks, 0, tm, kpre, false, later, stage);
+        if (blk == keep_blk) k_tile<G, false>(a, b, h, blk, len_k, ks, 0, tm, kpre, false, later, stage, lds_lg, lds_tokens);
+        else k_tile<G, true>(a, b, h, blk, len_k, ks, 0, tm, kpre, false, later, stage, lds_lg, lds_tokens);
         blk += 1;
         fold(tm);
     }
@@ -162,7 +170,8 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
         float m = -INFINITY;
         if (attend_new) {   // after the barrier: the tile that covers position len_old has stored its vector
             m = ks.new_logit[tid];
-            a.logits[(size_t(b) * Hq + size_t(h) * G + tid) * Ncap + len_old] = m;
+            if (LDSLG) lds_lg[tid * lds_tokens + len_old] = m;
+            if (!LDSLG || a.dbg.logits) a.logits[(size_t(b) * Hq + size_t(h) * G + tid) * Ncap + len_old] = m;
         }
         for (int w = 0; w < kWaves; ++w) m = fmaxf(m, wmax_s[tid][w]);
         ms.M[tid] = m;
@@ -178,7 +187,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
             for (int i = 0; i < 4; ++i)
                 if ((len_old & 3) == i) own[g][i] = ks.new_logit[g];
     }
-    mid_step<G, NT>(a, b, h, len, ms, own, own_ok);
+    mid_step<G, NT>(a, b, h, len, ms, own, own_ok, lds_lg, lds_tokens);
 
     // ---- V side: each wave walks its range of batches of 8*KG rows -------------------------------------
     VRule vr;
@@ -193,7 +202,7 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
     }
-    v_rows<G, KG, DEBUG, kHeadVPre, kHeadVPre>(a, b, h, vb0 * RB, RB, vb1 - vb0, len, vr, Mg, acc, z, pre, pre_ok);
+    v_rows<G, KG, DEBUG, kHeadVPre, kHeadVPre>(a, b, h, vb0 * RB, RB, vb1 - vb0, len, vr, Mg, acc, z, pre, pre_ok, lds_lg, lds_tokens);
     v_reduce_rows<G>(acc, z);
     if (r == 0) {
 #pragma unroll
@@ -217,12 +226,32 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a)
     finish_append(a, b, len_old, ticket);
 }
 
+// bytes of LDS a head workgroup may spend on logits beside its static arrays (staging areas of the K tiles, mid step,
+// reduction): 160 KB per compute unit, one workgroup of 1024 threads or two of 512
+template <int NT> constexpr size_t head_lds_logit_budget() { return NT >= 1024 ? 48 * 1024 : 32 * 1024; }
+
 template <int G, int NT>
 static hipError_t launch_head_g(const DecodeArgs& a, hipStream_t st)
 {
     const dim3 grid(xcd_grid(size_t(a.s.B) * a.s.Hkv)), block(NT);
-    if (a.dbg.needV || a.dbg.appliedV || a.stats) hipLaunchKernelGGL((head_kernel<G, NT, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((head_kernel<G, NT, false>), grid, block, 0, st, a);
+    const bool debug = a.dbg.needV || a.dbg.appliedV || a.stats;
+    const int lds_tokens = (std::min(a.max_len, a.s.Ncap) + kTB - 1) / kTB * kTB;   // the K tiles write whole blocks
+    const size_t lds_bytes = size_t(G) * lds_tokens * sizeof(float);
+    if (lds_bytes <= head_lds_logit_budget<NT>()) {
+        static bool raised = false;   // per instantiation: allow the dynamic part beside the static arrays
+        auto kd = head_kernel<G, NT, true, true>;
+        auto kp = head_kernel<G, NT, false, true>;
+        if (!raised) {
+            if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)head_lds_logit_budget<NT>())) return e;
+            if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kp), hipFuncAttributeMaxDynamicSharedMemorySize, (int)head_lds_logit_budget<NT>())) return e;
+            raised = true;
+        }
+        if (debug) hipLaunchKernelGGL(kd, grid, block, lds_bytes, st, a, lds_tokens);
+        else hipLaunchKernelGGL(kp, grid, block, lds_bytes, st, a, lds_tokens);
+    } else {
+        if (debug) hipLaunchKernelGGL((head_kernel<G, NT, true, false>), grid, block, 0, st, a, 0);
+        else hipLaunchKernelGGL((head_kernel<G, NT, false, false>), grid, block, 0, st, a, 0);
+    }
     return hipGetLastError();
 }
 

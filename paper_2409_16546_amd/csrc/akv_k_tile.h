@@ -167,10 +167,13 @@ __device__ __forceinline__ void k_tile_pre(const DecodeArgs& a, int b, int h, in
 
 // NT: the block's bytes are read with the non-temporal hint (they are read once per step); a caller that is about to
 // store into the block's lines (fused append) reads that one block without it, so that the lines stay in L2.
+// lds_lg: where a kernel keeps the logits of its (sequence, KV head) in LDS (query head g at lds_lg + g * lds_stride
+// floats, token t at index t), or NULL: they go to a.logits.  With LDS logits a.logits is written as well only if it
+// is the caller's export buffer (a.dbg.logits).
 template <int G, bool NT = true>
 __device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int blk, int len, const KShared<G>& ks,
                                        int aux, float (&tile_max)[G], const u32x4_t (&pre)[6], bool use_pre,
-                                       float (&acc)[G][4], uint8_t* stage)
+                                       float (&acc)[G][4], uint8_t* stage, float* lds_lg = nullptr, int lds_stride = 0)
 {
     constexpr int U = kKU;
     constexpr int kAux = NT ? kAuxNt : 0;
@@ -292,8 +295,11 @@ __device__ __forceinline__ void k_tile(const DecodeArgs& a, int b, int h, int bl
         u32x4_t w;
         w.x = float_bits(acc[g][0]); w.y = float_bits(acc[g][1]);
         w.z = float_bits(acc[g][2]); w.w = float_bits(acc[g][3]);
-        if (aux) __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, uint32_t(t0) * 4u, 0, kAuxSc1);
-        else __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, uint32_t(t0) * 4u, 0, 0);
+        if (lds_lg) *reinterpret_cast<u32x4_t*>(lds_lg + g * lds_stride + t0) = w;
+        if (!lds_lg || a.dbg.logits) {
+            if (aux) __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, uint32_t(t0) * 4u, 0, kAuxSc1);
+            else __builtin_amdgcn_raw_buffer_store_b128(w, rs_lg, uint32_t(t0) * 4u, 0, 0);
+        }
         float m = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i)

@@ -220,9 +220,11 @@ __device__ __forceinline__ void mid_oest(const DecodeArgs& a, size_t bh, size_t 
 // without a second barrier; ballots order the tokens inside the wave.  The selected V rows are fetched by all
 // threads at once into LDS so that O_est costs one memory latency, then each channel runs its ordered FMA chain
 // from operands fetched up front.  Results: a.M, a.Ehat (global, for a later kernel) and sm.ehat (LDS).
+// lds_lg / lds_stride: the logits in LDS as k_tile left them, or NULL (they are read from a.logits).
 template <int G, int NT>
 __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int len, MidShared& sm,
-                                         const float (&own)[G][4], bool use_own)
+                                         const float (&own)[G][4], bool use_own, const float* lds_lg = nullptr,
+                                         int lds_stride = 0)
 {
     constexpr int kWaves = NT / 64;
     constexpr int kChunk = NT * 4;
@@ -241,6 +243,7 @@ __device__ __forceinline__ void mid_step(const DecodeArgs& a, int b, int h, int 
         const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
         const __amdgpu_buffer_rsrc_t rs_lg = make_rsrc(a.logits + hq * Ncap, uint32_t(Ncap) * 4u);
         auto load4 = [&](int t0) -> float4 {   // Ncap % 256 == 0: the vector stays inside the row
+            if (lds_lg) return *reinterpret_cast<const float4*>(lds_lg + g * lds_stride + t0);
             const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rs_lg, uint32_t(t0) * 4u, 0, 0);
             return make_float4(bits_float(w.x), bits_float(w.y), bits_float(w.z), bits_float(w.w));
         };

@@ -92,13 +92,15 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 // is forced to zero.  acc accumulates sum_t p_t * v~_td per lane (to be reduced over the 8 row lanes, then
 // over waves, by the caller); z accumulates sum_t p_t per lane (to be summed over all 64 lanes).
 // NPRE > 0: pre holds the HI bytes of batches 0 .. NPRE-1 (v_prefetch_hi) if pre_ok.
+// lds_lg / lds_stride: the logits in LDS (query head g at lds_lg + g * lds_stride, token t at index t), or NULL: a.logits.
 // NT: the HI bytes are read with the non-temporal hint (measured: it pays in the token-split V kernel, where the logits
 // and the chunk partials of other workgroups share the caches, and costs in the head-per-workgroup kernel); the MID
 // and LO bytes always are (it pays in both).
 template <int G, int KG, bool DEBUG, int NPRE, int DL = 2, bool NT = false>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
                                        int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
-                                       float (&z)[G], const u32x4_t (&pre)[NPRE > 0 ? NPRE : 1][KG], bool pre_ok)
+                                       float (&z)[G], const u32x4_t (&pre)[NPRE > 0 ? NPRE : 1][KG], bool pre_ok,
+                                       const float* lds_lg = nullptr, int lds_stride = 0)
 {
     constexpr int RB = 8 * KG;
     // wave-uniform by contract: scalar registers, scalar loop control
@@ -147,7 +149,8 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
     };
     auto Llg = [&](Batch& X, int bt) {   // one load for all heads; rows at or past len and idle lanes ask out of range
         const bool on = bt < nbatches && jlane && row0(bt) + jrow < len;
-        X.lg = bits_float(buf_load_b32(rs_lg, on ? voff_lg + uint32_t(row0(bt)) * 4u : kSkip));
+        if (lds_lg) X.lg = on ? lds_lg[jg * lds_stride + row0(bt) + jrow] : 0.0f;   // uniform branch: the kernel keeps its logits in LDS
+        else X.lg = bits_float(buf_load_b32(rs_lg, on ? voff_lg + uint32_t(row0(bt)) * 4u : kSkip));
     };
     auto D = [&](Batch& X, int bt) {
         uint32_t offm[KG], offl[KG];

@@ -438,12 +438,13 @@ def test_append_decode_in_one_call_across_block_chunk_and_prefetch_boundaries(T,
         assert torch.equal(gc2_out, out)
 
 
-@pytest.mark.parametrize("cfg,path", [(1, 0), (2, 0), (3, 0), (3, 1), (4, 0), (5, 0)],
-                         ids=["cfg1", "cfg2", "cfg3", "cfg3-head-path", "cfg4", "cfg5"])
+@pytest.mark.parametrize("cfg,path", [(1, 0), (2, 0), (3, 0), (3, 2), (4, 0), (5, 0)],
+                         ids=["cfg1", "cfg2", "cfg3", "cfg3-split-path", "cfg4", "cfg5"])
 def test_full_size_configurations_against_the_oracle_everywhere(T, cfg, path):
     """The five benchmark configurations at full size, in the launch configuration the benchmark times (max_len = the
     longest sequence, the library's choice of path, no exports in the timed call; config 3 with its last token appended
-    inside the step, and also on the head-per-workgroup kernel: fused append, two blocks per wave).  The oracle runs the
+    inside the step -- the library takes the head-per-workgroup kernel there: fused append, two rounds of pairs, two
+    blocks per wave, logits in LDS -- and also on the token-split kernels).  The oracle runs the
     WHOLE configuration: every plane byte, every lvlK, logit, score exponent, selection, O_est, result exponent, needV
     and appliedV of every (sequence, head) is compared bit for bit, every output within the tolerance, and the device
     counters with the oracle's counts."""

@@ -32,7 +32,7 @@ def test_static_scratch_entry_point_matches_the_workspace_entry_point_on_two_cal
         A.akv_decode_attention_static(gc, q, out_st, dbg=d_st, path=path, stats=s_st)
         A.akv_decode_attention_static(gc, q, plain_st, path=path)       # and the variant without exports
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before                    # nothing was allocated through torch either
+        assert torch.cuda.memory_allocated() <= before                    # nothing was allocated through torch either
         assert torch.equal(out_ws, out_st) and torch.equal(out_ws, plain_st)
         for name in ("lvlK", "logits", "a", "sel", "oest", "Ehat", "needV", "appliedV"):
             x, y = getattr(d_ws, name), getattr(d_st, name)

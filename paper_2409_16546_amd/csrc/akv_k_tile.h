@@ -11,7 +11,7 @@ namespace akv {
 template <int G>
 struct KShared {
     float q[G][kD];
-    int emax[G];
+    int emax[2][G];                     // largest addend exponent per query head, of the columns of wave 0 / wave 1
     uint64_t need_mid[2], need_lo[2];   // bit d%64 of word d/64: column d is read at level >= 1 / = 2
     float knew[kD];                     // fused append: the new token's K row as it will be read at the column levels
     float new_logit[G];                 // fused append: q . knew, accumulated in channel order
@@ -52,11 +52,9 @@ __device__ __forceinline__ uint32_t k_levels_finish(const DecodeArgs& a, int b, 
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t bh = size_t(b) * a.s.Hkv + h;
-    if (tid < G) ks.emax[tid] = -1;
-    __syncthreads();
     float P[G];
     uint32_t colmax_used = 0;
-    if (tid < kD) {
+    if (tid < kD) {   // waves 0 and 1 (wave-uniform): channel tid
         uint32_t cm = in.cm;
         if (k_new_bits >= 0) cm = max(cm, uint32_t(k_new_bits) & 0x7FFFu);
         colmax_used = cm;
@@ -67,16 +65,20 @@ __device__ __forceinline__ uint32_t k_levels_finish(const DecodeArgs& a, int b, 
             const float qf = half_bits_to_float(in.qbits[g]);
             ks.q[g][tid] = qf;
             P[g] = qf * cmf;                             // exact: 11-bit x 11-bit significands
-            if (P[g] != 0.0f) atomicMax(&ks.emax[g], float_exp_field(P[g]));
+            // the maximum over the wave's 64 columns in the vector ALU (LDS atomics of 64 lanes on one address take a
+            // cycle per lane of the LDS unit that all workgroups of the compute unit share)
+            const int em = wave_max_int(P[g] != 0.0f ? float_exp_field(P[g]) : -1);
+            if (lane == 0) ks.emax[wave][g] = em;
         }
     }
     __syncthreads();
-    if (tid < kD) {   // waves 0 and 1: channel tid
+    if (tid < kD) {
         int lv = 0;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (P[g] != 0.0f) {
-                const int l = level_for_mantissa_bits(10 + a.guard_bits - (ks.emax[g] - float_exp_field(P[g])));
+                const int emax = max(ks.emax[0][g], ks.emax[1][g]);
+                const int l = level_for_mantissa_bits(10 + a.guard_bits - (emax - float_exp_field(P[g])));
                 lv = l > lv ? l : lv;
             }
         }

@@ -164,14 +164,15 @@ def main():
             ev.destroy(pr)
         return gap
 
-    def bytes_from_stats(st, w, lens, with_append):
-        """Algorithmic bytes of one step from the library's device counters (elements per level)."""
+    def bytes_from_stats(st, w, lens, with_append, logits_in_memory=True):
+        """Algorithmic bytes of one step from the library's device counters (elements per level).  logits_in_memory:
+        false where the head-per-workgroup kernel keeps its logits in LDS (akv_decode_path() == 3)."""
         k, v = st[0:3], st[3:6]
         k_planes = int(k.sum()) + int(k[1] + k[2]) // 2 + int(k[2]) // 2
         v_planes = int(v.sum()) + int(v[1] + v[2]) // 2 + int(v[2]) // 2
         ntok = int(sum(lens))
-        logits_w = 4 * ntok * w.Hq                       # written by the K side
-        logits_r = 4 * ntok * w.Hq                       # read by the V side (the mid step's read is served by the caches)
+        logits_w = 4 * ntok * w.Hq if logits_in_memory else 0   # written by the K side
+        logits_r = 4 * ntok * w.Hq if logits_in_memory else 0   # read by the V side (the mid step's read is served by the caches)
         oest = w.B * w.Hq * 32 * w.D * 2                 # the top-k rows of V at 16 bits
         small = w.B * w.Hq * w.D * 2 + w.B * w.Hkv * w.D * 2 + w.B * w.Hq * w.D * 4
         if with_append:
@@ -196,7 +197,7 @@ def main():
         plane_bytes = 2 * B * Hkv * N * D * 2
         R = max(2, min(64, -(-(2 << 30) // plane_bytes)))       # copies: the rotating footprint passes 2 GB
         path = A.akv_decode_path(B, Hq, Hkv, D, N, maxlen)      # the library's own choice for this shape
-        prof_steps = 0 if path == 1 else max(10, min(steps, 50))  # second pass with events between the kernels (token-split path)
+        prof_steps = 0 if path != 2 else max(10, min(steps, 50))  # second pass with events between the kernels (token-split path)
         if headline:
             R = max(R, (steps + warmup + prof_steps + 255) // 256)
         visits = (steps + warmup + prof_steps + R - 1) // R if append else 0  # times each cache copy is stepped
@@ -258,7 +259,7 @@ def main():
             seg = [max(0.0, sum(ev.elapsed_ms(e[k], e[k + 1]) for e in evs) * 1e3 / prof_steps - gap) for k in range(A.AKV_NEVENTS - 1)]
             for e in evs:
                 ev.destroy(e)
-        one_kernel = path == 1
+        one_kernel = path != 2
         if append:
             for c in caches:
                 assert int(c.flags[0]) == 0 and int(c.flags[1]) == 0
@@ -267,13 +268,14 @@ def main():
         st = A.new_stats(dev)
         out_stats = A.akv_decode_attention(caches[0], qd, stats=st, **kw).clone()
         torch.cuda.synchronize()
-        by = bytes_from_stats(st.cpu().numpy().astype(np.int64), w, lens, append)
+        by = bytes_from_stats(st.cpu().numpy().astype(np.int64), w, lens, append, logits_in_memory=path != 3)
         entry["us_per_step"] = round(us_step, 2)
         entry["us_per_step_hip_events"] = round(us_events, 2)
         if one_kernel:
-            entry["path"] = "head-per-workgroup (one kernel)"
+            entry["path"] = "head-per-workgroup (one kernel" + ("; logits in LDS)" if path == 3 else ")")
             entry["kernel_us"] = {"head_kernel": round(us_events, 2)}
-            dom_name, dom_tag, dom_us, dom_bytes = f"akv::head_kernel<{Hq // Hkv}, {1024 if Hq == Hkv else 512}, false>", "head_kernel", us_events, by["total"]
+            dom_name = f"akv::head_kernel<{Hq // Hkv}, {1024 if Hq == Hkv else 512}, false, {'true' if path == 3 else 'false'}>"
+            dom_tag, dom_us, dom_bytes = "head_kernel", us_events, by["total"]
         else:
             entry["path"] = "token-split (K, slice, selection, V kernels" + ("; append kernel in front)" if append else ")")
             entry["kernel_us"] = {"append": round(seg[0], 2), "k_kernel": round(seg[1], 2), "slice_and_selection": round(seg[2], 2),
@@ -296,8 +298,9 @@ def main():
                 "traffic_source": (traffic_src + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy; a committed "
                                    "figure, not measured in this run)") if traffic else None,
                 "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2),
-                "logits_bytes_counted": "4 B per (query head, token) written by the K side and 4 B read by the V side; the mid "
-                                        "step's read of the same logits is left out (served by the caches)"}
+                "logits_bytes_counted": ("4 B per (query head, token) written by the K side and 4 B read by the V side; the mid "
+                                         "step's read of the same logits is left out (served by the caches)") if path != 3 else
+                                        "none: the kernel keeps its logits in LDS"}
         entry["roofline"] = roof
         log(f"[bench] cfg{cfg}: {us_step:.1f} us/step ({entry['path']}); kernels {entry['kernel_us']}; K {by['avg_bits_K']} / V "
             f"{by['avg_bits_V_rows']} bits; {by['total'] / 1e6:.1f} MB vs fp16 {by['fp16'] / 1e6:.1f} MB "
@@ -318,7 +321,7 @@ def main():
             st2 = A.new_stats(dev)
             A.akv_decode_attention(caches[0], qd, guard_bits=2, max_len=maxlen, stats=st2)
             torch.cuda.synchronize()
-            by2 = bytes_from_stats(st2.cpu().numpy().astype(np.int64), w, lens, False)
+            by2 = bytes_from_stats(st2.cpu().numpy().astype(np.int64), w, lens, False, logits_in_memory=path != 3)
             hot = timed(lambda i: A.akv_decode_attention(caches[0], qd, outs[0], **kw), n)
             keep = caches[0]
             del caches[1:]

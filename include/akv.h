@@ -206,8 +206,9 @@ akv_status akv_decode_attention(const akv_cache *cache, const uint16_t *q, void 
                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /* Which kernels akv_decode_attention takes for this shape when params->path is 0: 1 = head-per-workgroup (one
- * kernel), 2 = token-split (four kernels); max_len as in akv_params (0 means Ncap).  Host computation; 0 on a bad
- * shape.  For callers that attribute time to kernels. */
+ * kernel, logits through the workspace), 3 = the same with the logits kept in LDS (none written to memory),
+ * 2 = token-split (four kernels); max_len as in akv_params (0 means Ncap).  Host computation; 0 on a bad shape.
+ * For callers that attribute time and bytes to kernels. */
 int32_t akv_decode_path(const akv_shape *shape, int32_t max_len);
 
 /*

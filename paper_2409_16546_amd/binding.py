@@ -258,7 +258,7 @@ class DebugBuffers:
 
 
 def akv_decode_path(B: int, Hq: int, Hkv: int, D: int, Ncap: int, max_len: int = 0) -> int:
-    """1 (head-per-workgroup kernel) or 2 (token-split kernels): what path=0 takes for this shape."""
+    """1 (head-per-workgroup kernel), 3 (the same, logits kept in LDS) or 2 (token-split kernels): what path=0 takes."""
     shp = akv_shape(B, Hq, Hkv, D, Ncap)
     return int(lib().akv_decode_path(C.byref(shp), max_len))
 

@@ -319,7 +319,8 @@ int32_t akv_decode_path(const akv_shape* shape, int32_t max_len)
 {
     if (!shape || !shape_ok(*shape) || max_len < 0 || max_len > shape->Ncap) return 0;
     const int ml = max_len > 0 ? max_len : shape->Ncap;
-    return akv::head_path_supported(*shape) && head_path_pays(long(shape->B) * shape->Hkv, shape->Hq / shape->Hkv, ml) ? 1 : 2;
+    if (!(akv::head_path_supported(*shape) && head_path_pays(long(shape->B) * shape->Hkv, shape->Hq / shape->Hkv, ml))) return 2;
+    return akv::head_logits_in_lds(*shape, ml) ? 3 : 1;
 }
 
 akv_status akv_decode_attention_static(const akv_cache* cache, const uint16_t* q, void* out, const akv_params* params,

@@ -156,6 +156,7 @@ hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, h
 hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t k_done_event, hipEvent_t mid_event);   // four kernels; the events (may be null) are recorded after the first and in front of the last
 hipError_t launch_decode_head(const DecodeArgs& a, hipStream_t st);                         // one kernel, a head per workgroup
 bool head_path_supported(const akv_shape& s);
+bool head_logits_in_lds(const akv_shape& s, int max_len);   // the head kernel keeps the logits of this shape in LDS (none written to memory)
 hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v, const int32_t* lens, const uint16_t* q,
                        void* out, float scale, int out_dtype, int max_len, void* ws, hipStream_t st);
 size_t fp16_workspace_bytes(const akv_shape& s);

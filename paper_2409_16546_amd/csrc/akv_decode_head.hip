@@ -230,14 +230,23 @@ __global__ __launch_bounds__(NT) void head_kernel(DecodeArgs a, int lds_tokens)
 // reduction): 160 KB per compute unit, one workgroup of 1024 threads or two of 512
 template <int NT> constexpr size_t head_lds_logit_budget() { return NT >= 1024 ? 48 * 1024 : 32 * 1024; }
 
+static int head_lds_tokens(const akv_shape& s, int max_len) { return (std::min(max_len, s.Ncap) + kTB - 1) / kTB * kTB; }   // the K tiles write whole blocks
+
+bool head_logits_in_lds(const akv_shape& s, int max_len)
+{
+    const int G = s.Hq / s.Hkv;
+    const size_t bytes = size_t(G) * head_lds_tokens(s, max_len) * sizeof(float);
+    return bytes <= (G == 1 ? head_lds_logit_budget<1024>() : head_lds_logit_budget<512>());
+}
+
 template <int G, int NT>
 static hipError_t launch_head_g(const DecodeArgs& a, hipStream_t st)
 {
     const dim3 grid(xcd_grid(size_t(a.s.B) * a.s.Hkv)), block(NT);
     const bool debug = a.dbg.needV || a.dbg.appliedV || a.stats;
-    const int lds_tokens = (std::min(a.max_len, a.s.Ncap) + kTB - 1) / kTB * kTB;   // the K tiles write whole blocks
+    const int lds_tokens = head_lds_tokens(a.s, a.max_len);
     const size_t lds_bytes = size_t(G) * lds_tokens * sizeof(float);
-    if (lds_bytes <= head_lds_logit_budget<NT>()) {
+    if (head_logits_in_lds(a.s, a.max_len)) {
         static bool raised = false;   // per instantiation: allow the dynamic part beside the static arrays
         auto kd = head_kernel<G, NT, true, true>;
         auto kp = head_kernel<G, NT, false, true>;

@@ -130,6 +130,17 @@ def test_static_scratch_entry_point_refuses_shapes_beyond_its_array(A):
     assert re.search(r"#define AKV_STATIC_SCRATCH_BYTES \((\d+)u << 20\)", text).group(1) == str(A.AKV_STATIC_SCRATCH_BYTES >> 20)
 
 
+def test_decode_path_query_is_a_host_computation(A):
+    # 256 compute units are assumed where no device can be asked
+    assert A.akv_decode_path(8, 32, 32, 128, 4096) == 3            # configuration 2: head kernel, logits in LDS
+    assert A.akv_decode_path(16, 32, 32, 128, 8192) == 3           # configuration 3: two full rounds of single heads
+    assert A.akv_decode_path(8, 32, 8, 128, 32768) == 2            # configuration 4: token-split kernels
+    assert A.akv_decode_path(8, 32, 32, 128, 16384) == 2           # too long for the head kernel to pay
+    assert A.akv_decode_path(8, 32, 32, 128, 16384, 4096) == 3     # ... unless the caller bounds the lengths
+    assert A.akv_decode_path(32, 32, 8, 128, 4096) == 1            # groups of four: 64 KB of logits do not fit the LDS share
+    assert A.akv_decode_path(1, 6, 2, 128, 256) == 0               # bad shape
+
+
 def test_misaligned_weight_arrays_are_refused(A):
     L = A.lib()
     w = A.akw_weights(64, 32, 0x10000, 0x20000, 0x30000, 0x40000)

@@ -89,7 +89,7 @@ struct DecodeArgs {
     int32_t* Ehat;
     float* partO;
     float* partZ;
-    int vchunk;          // tokens per workgroup of the V kernel of the token-split path (multiple of kVChunk)
+    int vchunk;          // tokens per workgroup of the V kernel of the token-split path (a multiple of 64: whole batches of rows for every wave; at least kVChunk)
     int32_t* hist;       // per-slice histograms of the token-split path
     int32_t* cand_sel;   // per-slice candidates of the token-split path
     float* cand_phat;

@@ -247,13 +247,15 @@ static hipError_t launch_head_g(const DecodeArgs& a, hipStream_t st)
     const int lds_tokens = head_lds_tokens(a.s, a.max_len);
     const size_t lds_bytes = size_t(G) * lds_tokens * sizeof(float);
     if (head_logits_in_lds(a.s, a.max_len)) {
-        static bool raised = false;   // per instantiation: allow the dynamic part beside the static arrays
+        static bool raised[64] = {};   // per instantiation and device: allow the dynamic part beside the static arrays
         auto kd = head_kernel<G, NT, true, true>;
         auto kp = head_kernel<G, NT, false, true>;
-        if (!raised) {
+        int dev = 0;
+        if (hipError_t e = hipGetDevice(&dev)) return e;
+        if (dev < 0 || dev >= 64 || !raised[dev]) {
             if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)head_lds_logit_budget<NT>())) return e;
             if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kp), hipFuncAttributeMaxDynamicSharedMemorySize, (int)head_lds_logit_budget<NT>())) return e;
-            raised = true;
+            if (dev >= 0 && dev < 64) raised[dev] = true;
         }
         if (debug) hipLaunchKernelGGL(kd, grid, block, lds_bytes, st, a, lds_tokens);
         else hipLaunchKernelGGL(kp, grid, block, lds_bytes, st, a, lds_tokens);

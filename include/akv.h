@@ -220,7 +220,9 @@ int32_t akv_decode_path(const akv_shape *shape, int32_t max_len);
  * AKV_EWORKSPACE and a text that names both sizes.  Every call on a GPU shares that GPU's array: calls that
  * overlap on one GPU (two streams, two threads) race; order them on one stream.  The control words the kernels
  * rely on lie at a fixed place at the front of the array, are zeroed by a fill kernel on the first call on each
- * device and are left at zero by every call, so a call may follow one of any other shape.
+ * device and are left at zero by every call, so a call may follow one of any other shape.  The first call on a device
+ * looks up the array's address (hipGetSymbolAddress): make that call before a stream capture begins; later calls
+ * enqueue kernels only and can be captured into a HIP graph and replayed.
  */
 #define AKV_STATIC_SCRATCH_BYTES (48u << 20)
 akv_status akv_decode_attention_static(const akv_cache *cache, const uint16_t *q, void *out, const akv_params *params,

@@ -45,7 +45,8 @@ typedef enum akv_status {
     AKV_OK = 0,
     AKV_EINVAL = 1,     /* bad shape, NULL pointer, parameter out of range   */
     AKV_EWORKSPACE = 2, /* workspace too small or misaligned (256 B)          */
-    AKV_EHIP = 3        /* a HIP launch failed; akv_last_error() has the text */
+    AKV_EHIP = 3,       /* a HIP launch failed; akv_last_error() has the text */
+    AKV_ECAPACITY = 4   /* akv_check_capacity_sync: an append of that many tokens would not fit */
 } akv_status;
 
 /* Problem shape.  Hq query heads share Hkv KV heads in groups of G = Hq/Hkv
@@ -183,6 +184,15 @@ akv_status akv_cache_reset(const akv_cache *cache, void *stream);
  */
 akv_status akv_append(const akv_cache *cache, const uint16_t *k_new, const uint16_t *v_new, const int32_t *n_new,
                       int32_t n, void *stream);
+
+/*
+ * Debugging aid, the one call that synchronises: waits for the work enqueued on `stream`, copies lens to the host and
+ * returns AKV_ECAPACITY (naming the first sequence in akv_last_error()) if an append of n tokens to every sequence
+ * would exceed Ncap for any of them, AKV_OK otherwise.  The appending calls themselves never synchronise: on the device
+ * a sequence that would overflow is left unchanged and counted in flags[AKV_FLAG_OVERFLOW] ("Dynamic Quantization":
+ * tokens are stored as they are produced; capacity is the caller's to provide).
+ */
+akv_status akv_check_capacity_sync(const akv_cache *cache, int32_t n, void *stream);
 
 /*
  * Prepare a decode workspace: zero its control words (arrival counters that the

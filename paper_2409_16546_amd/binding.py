@@ -15,14 +15,15 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libakv.so")
 
-AKV_OK, AKV_EINVAL, AKV_EWORKSPACE, AKV_EHIP = 0, 1, 2, 3
+AKV_OK, AKV_EINVAL, AKV_EWORKSPACE, AKV_EHIP, AKV_ECAPACITY = 0, 1, 2, 3, 4
 AKV_TB = 256
 AKV_NFLAGS = 4
 AKV_FLAG_OVERFLOW, AKV_FLAG_MAXLEN = 0, 1
 AKV_MAX_TOPK = 64
 AKV_NEVENTS = 5
 AKV_STATIC_SCRATCH_BYTES = 48 << 20
-EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_workspace_init",
+EXPORTS = ["akv_version", "akv_last_error", "akv_layout_sizes", "akv_cache_reset", "akv_append", "akv_check_capacity_sync",
+           "akv_workspace_init",
            "akv_decode_attention", "akv_decode_path", "akv_decode_attention_static", "akv_append_decode_attention", "akv_unpack", "akv_fp16_decode_attention", "akv_stream_read",
            "akw_layout_sizes", "akw_workspace_init", "akw_pack", "akw_unpack", "akw_gemv"]
 AKW_MAX_B = 4
@@ -93,6 +94,8 @@ def lib() -> C.CDLL:
         L.akv_cache_reset.argtypes = [C.POINTER(akv_cache), C.c_void_p]
         L.akv_append.restype = C.c_int
         L.akv_append.argtypes = [C.POINTER(akv_cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.akv_check_capacity_sync.restype = C.c_int
+        L.akv_check_capacity_sync.argtypes = [C.POINTER(akv_cache), C.c_int32, C.c_void_p]
         L.akv_workspace_init.restype = C.c_int
         L.akv_workspace_init.argtypes = [C.POINTER(akv_shape), C.c_void_p, C.c_size_t, C.c_void_p]
         L.akv_decode_attention.restype = C.c_int
@@ -215,6 +218,12 @@ def akv_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, n_new: to
         assert n_new.dtype == torch.int32 and tuple(n_new.shape) == (cache.B,)
     s = cache.struct()
     _check(lib().akv_append(C.byref(s), _ptr(k_new), _ptr(v_new), _ptr(n_new), n, _stream()))
+
+
+def akv_check_capacity_sync(cache: Cache, n: int) -> None:
+    """Debugging aid (synchronises): raises AkvError(AKV_ECAPACITY) if n more tokens would not fit some sequence."""
+    s = cache.struct()
+    _check(lib().akv_check_capacity_sync(C.byref(s), n, _stream()))
 
 
 def akv_stream_read(buf: torch.Tensor, sink: torch.Tensor) -> None:

@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 #include "akv_common.h"
 
@@ -127,6 +128,21 @@ akv_status akv_append(const akv_cache* cache, const uint16_t* k_new, const uint1
     if (!aligned16(k_new) || !aligned16(v_new)) return fail(AKV_EINVAL, "k_new / v_new must be 16-byte aligned");
     if (hipError_t e = akv::launch_append(*cache, k_new, v_new, n_new, n, static_cast<hipStream_t>(stream)))
         return hip_fail(e, "append launch");
+    return AKV_OK;
+}
+
+akv_status akv_check_capacity_sync(const akv_cache* cache, int32_t n, void* stream)
+{
+    if (akv_status st = check_cache(cache)) return st;
+    if (n < 0) return fail(AKV_EINVAL, "n = %d is negative", n);
+    const int B = cache->shape.B;
+    std::vector<int32_t> lens(B);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipError_t e = hipMemcpyAsync(lens.data(), cache->lens, size_t(B) * sizeof(int32_t), hipMemcpyDeviceToHost, s)) return hip_fail(e, "hipMemcpyAsync");
+    if (hipError_t e = hipStreamSynchronize(s)) return hip_fail(e, "hipStreamSynchronize");
+    for (int b = 0; b < B; ++b)
+        if (long(lens[b]) + n > cache->shape.Ncap)
+            return fail(AKV_ECAPACITY, "sequence %d holds %d tokens: %d more exceed the capacity of %d", b, lens[b], n, cache->shape.Ncap);
     return AKV_OK;
 }
 

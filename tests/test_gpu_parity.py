@@ -71,6 +71,11 @@ def test_append_token_by_token_and_capacity_flag(T):
     torch.cuda.synchronize()
     assert refused >= 1 and int(gc.flags.cpu()[0]) == refused
     T.assert_cache_equal(gc, oc)
+    # the synchronising debug helper says the same on the host, before anything is enqueued
+    A.akv_check_capacity_sync(gc, Ncap - int(oc.lens.max()))
+    with pytest.raises(A.AkvError) as e:
+        A.akv_check_capacity_sync(gc, Ncap - int(oc.lens.max()) + 1)
+    assert e.value.status == A.AKV_ECAPACITY and "capacity" in str(e.value)
 
 
 def test_append_prefill_after_unaligned_lengths(T):

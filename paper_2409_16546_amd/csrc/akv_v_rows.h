@@ -86,7 +86,7 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 //      Rule 2 on the HI bytes; MID / LO loads of the rows that need them (the others are issued out of
 //      range: nothing is fetched);
 //   F  assemble the fp16 values, multiply-adds.
-// Round i runs L(i+DL), D(i+1), F(i): every load has at least a whole round of arithmetic to arrive; a kernel
+// Round i runs D(i+1), L(i+DL), F(i): every load has at least a whole round of arithmetic to arrive; a kernel
 // with few waves per SIMD raises DL to keep enough bytes in flight.
 // The descriptors end at row len, so rows at or past len read as zero without any per-lane test; their weight
 // is forced to zero.  acc accumulates sum_t p_t * v~_td per lane (to be reduced over the 8 row lanes, then
@@ -254,8 +254,11 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
         }
     };
 
-    // R = DL + 1 named buffers: round i runs L(i + DL), D(i + 1), F(i); the buffer L fills is the one F emptied in
-    // the round before.  The loop is unrolled R times so that every buffer index is a constant.
+    // R = DL + 1 named buffers: round i runs D(i + 1), L(i + DL), F(i); the buffer L fills is the one F emptied in
+    // the round before.  The loop is unrolled R times so that every buffer index is a constant.  Loads come back in
+    // the order they were issued, so the wait of F(i) for its MID / LO bytes (asked for by D(i), one round earlier) is
+    // also a wait for every load issued before them: D issues ahead of L in a round, so that this never includes the HI
+    // bytes L asked for in that round.
     constexpr int R = DL + 1;
     static_assert(DL >= 2 && NPRE <= DL, "the HI loads run at least two batches ahead");
     Batch ring[R];
@@ -275,9 +278,9 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
     for (int i = 0; i < nbatches; i += R) {   // rounds past the last batch issue nothing and compute nothing
 #pragma unroll
         for (int k = 0; k < R; ++k) {
+            D(ring[(k + 1) % R], i + k + 1);
             Lhi(ring[(k + DL) % R], i + k + DL);
             Llg(ring[(k + DL) % R], i + k + DL);
-            D(ring[(k + 1) % R], i + k + 1);
             F(ring[k], i + k);
         }
     }

@@ -213,7 +213,7 @@ bool head_path_pays(long pairs, int G, int max_len)
     const double fill = double(pairs) / double(cus);
     if (G == 1) return (max_len <= 8192 && fill >= 0.72) || (max_len <= 12288 && fill >= 0.85);
     if (G == 2) return max_len <= 8192 && fill >= 0.9;
-    return (max_len <= 4096 && fill >= 0.72) || (max_len <= 8192 && fill >= 0.95);
+    return (max_len <= 2048 && fill >= 0.6) || (max_len <= 4096 && fill >= 0.85) || (max_len <= 6144 && fill >= 0.97);
 }
 
 // decode attention, optionally preceded by the append of one token per sequence (k_new, v_new: [B][Hkv][D])
@@ -269,7 +269,7 @@ akv_status decode_impl(const akv_cache* cache, const uint16_t* k_new, const uint
         // the fixed costs per workgroup (Rule 2 constants, pipeline start, partial results) are paid once per slot
         const int cus = compute_units();
         const int G = a.s.Hq / a.s.Hkv;
-        const int per_cu = G <= 1 ? 4 : (G <= 2 ? 3 : (G <= 4 ? 2 : 1));   // resident V workgroups per compute unit (register budget)
+        const int per_cu = akv::split_v_workgroups_per_cu(G);
         const long pairs = long(a.s.B) * a.s.Hkv;
         const long per_pair = std::max(1L, long(cus) * per_cu / pairs);
         long chunk = (a.max_len + per_pair - 1) / per_pair;

@@ -155,6 +155,7 @@ hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t* sink, hipSt
 hipError_t launch_unpack(const akv_cache& c, uint16_t* k_out, uint16_t* v_out, hipStream_t st);
 hipError_t launch_decode_split(const DecodeArgs& a, hipStream_t st, hipEvent_t k_done_event, hipEvent_t mid_event);   // four kernels; the events (may be null) are recorded after the first and in front of the last
 hipError_t launch_decode_head(const DecodeArgs& a, hipStream_t st);                         // one kernel, a head per workgroup
+int split_v_workgroups_per_cu(int G);   // resident workgroups of the token-split V kernel per compute unit (registers, LDS)
 bool head_path_supported(const akv_shape& s);
 bool head_logits_in_lds(const akv_shape& s, int max_len);   // the head kernel keeps the logits of this shape in LDS (none written to memory)
 hipError_t launch_fp16(const akv_shape& s, const uint16_t* k, const uint16_t* v, const int32_t* lens, const uint16_t* q,

@@ -6,6 +6,7 @@
 //                     O_est and the result exponents;
 //   V kernel          Rule 2 + S.V~ over chunks of tokens; the workgroup that finishes last combines the chunks.
 // Sections "Quantization of K-Cache", "Quantization of V-Cache", "Runtime of AlignedKV".
+#include <type_traits>
 #include "akv_common.h"
 #include "akv_k_tile.h"
 #include "akv_mid_step.h"
@@ -285,11 +286,18 @@ __global__ __launch_bounds__(256) void split_select_kernel(DecodeArgs a)
 }
 
 // Workgroup = kVWaves waves, one (sequence, KV head, kVChunk-token chunk); wave w takes the batches of rows
-// w, w + kVWaves, ... of the chunk.
+// w, w + kVWaves, ... of the chunk.  Groups of four or eight query heads run v_rows in its shared mode: every wave
+// fetches and assembles its rows once, the rows pass through LDS, and wave w sums them for its share of the heads.
+template <int G> constexpr bool v_shared() { return G >= kVWaves; }
 template <int G, bool DEBUG>
 __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 {
-    __shared__ float red_s[kVWaves][G][kD + 1];
+    constexpr bool SHARED = v_shared<G>();
+    constexpr int GA = SHARED ? G / kVWaves : G;            // query heads a wave sums for
+    constexpr int KG = G >= 8 ? 1 : 2, RB = 8 * KG;         // one lane per (row of the batch, query head): at most 64 / G rows
+    __shared__ float red_s[SHARED ? 1 : kVWaves][G][kD + 1];
+    __shared__ float z_s[kVWaves][G];
+    __shared__ std::conditional_t<SHARED, VShare<G, RB>, int> share_s;
     __shared__ int last_s;
 
     const int h = blockIdx.y, b = blockIdx.z, split = blockIdx.x;
@@ -313,33 +321,39 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     float Mg[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) Mg[g] = a.M[size_t(b) * Hq + size_t(h) * G + g];
-    float acc[G][16], z[G];
+    float acc[GA][16], z[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        z[g] = 0.0f;
+    for (int g = 0; g < G; ++g) z[g] = 0.0f;
+#pragma unroll
+    for (int g = 0; g < GA; ++g)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
-    }
-    // 16 rows per batch, HI bytes fetched four batches ahead: the accumulators of a group of query heads leave room
-    // for few waves per SIMD, so each wave keeps more bytes in flight
-    constexpr int KG = G >= 8 ? 1 : 2, RB = 8 * KG, DL = G == 2 ? 4 : 3;
+    // HI bytes fetched three or four batches ahead: the accumulators of a group of query heads leave room for few waves
+    // per SIMD, so each wave keeps more bytes in flight
+    constexpr int DL = G == 2 ? 4 : 3;
     const u32x4_t none[1][KG] = {};
-    v_rows<G, KG, DEBUG, 0, DL, true>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
-    v_reduce_rows<G>(acc, z);
+    if constexpr (SHARED)
+        v_rows<G, KG, DEBUG, 0, DL, true, GA>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false, nullptr, 0, &share_s);
+    else
+        v_rows<G, KG, DEBUG, 0, DL, true>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
+    v_reduce_rows<GA>(acc, z);
     if (r == 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
+        for (int g = 0; g < GA; ++g) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) red_s[wave][g][cl * 16 + i] = acc[g][i];
-            if (cl == 0) red_s[wave][g][kD] = z[g];
+            for (int i = 0; i < 16; ++i) red_s[SHARED ? 0 : wave][SHARED ? wave * GA + g : g][cl * 16 + i] = acc[g][i];
         }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) z_s[wave][g] = z[g];
     }
     __syncthreads();
     for (int idx = tid; idx < G * (kD + 1); idx += 64 * kVWaves) {
         const int g = idx / (kD + 1), d = idx % (kD + 1);
         float s = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kVWaves; ++w) s += red_s[w][g][d];
+        for (int w = 0; w < kVWaves; ++w) s += d == kD ? z_s[w][g] : (SHARED && w > 0 ? 0.0f : red_s[SHARED ? 0 : w][g][d]);
         const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
         if (d < kD) store_agent(&a.partO[(hq * nsplit + split) * kD + d], s);
         else store_agent(&a.partZ[hq * nsplit + split], s);
@@ -374,6 +388,13 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
         store_out(a, hq, d, o / zsum);
     }
     if (tid == 0) store_agent(&a.vcount[bh], 0);   // ready for the next call
+}
+
+// what the register and LDS budgets of split_v_kernel<G> leave room for
+int split_v_workgroups_per_cu(int G)
+{
+    if (G >= kVWaves) return 4;   // shared mode: 16 or 32 sums per lane, 37 KB of LDS
+    return G <= 1 ? 4 : (G <= 2 ? 3 : (G <= 4 ? 2 : 1));
 }
 
 template <int G>

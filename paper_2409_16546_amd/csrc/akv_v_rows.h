@@ -76,6 +76,16 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
         for (int gr = 0; gr < KG; ++gr) hi[n][gr] = buf_load_b128(rs_hi, voff + uint32_t(n * batch_stride + gr * 8) * kD);
 }
 
+// LDS of the shared mode of v_rows: the rows all waves of a workgroup assembled in one round (fp16 pairs as
+// assemble8_fill leaves them: words 0..31 the first eight channels of the eight 16-channel slices, words 32..63 the
+// second eight) and the weights of these rows for every query head, in two buffers that alternate by round.
+template <int G, int RB> struct VShare {
+    alignas(16) uint32_t v[2][kVWaves * RB][64];
+    float p[2][kVWaves * RB][G];
+};
+// workgroup barrier that waits for this wave's LDS traffic only: the loads from memory that are in flight stay in flight
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // One wave walks token rows of (b, h) in batches of 8*KG rows (KG groups of 8 rows; lane -> row lane/8 of the
 // group and the 16-channel slice lane%8): batch i covers rows t_first + i*batch_stride .. + 8*KG - 1,
 // i < nbatches.  Three stages per batch, software-pipelined over DL + 1 named buffers:
@@ -96,13 +106,21 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
 // NT: the HI bytes are read with the non-temporal hint (measured: it pays in the token-split V kernel, where the logits
 // and the chunk partials of other workgroups share the caches, and costs in the head-per-workgroup kernel); the MID
 // and LO bytes always are (it pays in both).
-template <int G, int KG, bool DEBUG, int NPRE, int DL = 2, bool NT = false>
+// GA < G, sh: the shared mode for groups of query heads.  Every wave of the workgroup still fetches, tests and
+// assembles its own rows, once, but leaves them in LDS with their weights; after a barrier wave w adds ALL rows of
+// the round into acc for the GA query heads w*GA .. w*GA + GA - 1 only.  The arithmetic per row is the same; a lane
+// holds 16*GA sums instead of 16*G, which is what lets twice as many waves be resident.  All waves of the workgroup
+// must call with the same nbatches.
+template <int G, int KG, bool DEBUG, int NPRE, int DL = 2, bool NT = false, int GA = G>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
-                                       int len, const VRule& vr, const float (&Mg)[G], float (&acc)[G][16],
+                                       int len, const VRule& vr, const float (&Mg)[G], float (&acc)[GA][16],
                                        float (&z)[G], const u32x4_t (&pre)[NPRE > 0 ? NPRE : 1][KG], bool pre_ok,
-                                       const float* lds_lg = nullptr, int lds_stride = 0)
+                                       const float* lds_lg = nullptr, int lds_stride = 0, VShare<G, 8 * KG>* sh = nullptr)
 {
     constexpr int RB = 8 * KG;
+    constexpr bool SHARED = GA != G;
+    static_assert(!SHARED || GA * kVWaves == G, "shared mode: the waves of a workgroup split the query heads of the group");
+    const int wave = threadIdx.x >> 6;
     // wave-uniform by contract: scalar registers, scalar loop control
     nbatches = __builtin_amdgcn_readfirstlane(nbatches);
     t_first = __builtin_amdgcn_readfirstlane(t_first);
@@ -137,7 +155,8 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
         u32x4_t hi[KG];
         float lg;
         u32x2_t mid[KG], lo[KG];
-        float p[KG][G];
+        float p[SHARED ? 1 : KG][SHARED ? 1 : G];
+        float pj;   // shared mode: the weight this lane computed, kept until the round of its batch
         uint32_t fill[KG];
     };
     auto row0 = [&](int bt) { return t_first + bt * batch_stride; };
@@ -163,6 +182,7 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
             int ahat = score_a(x);                      // then the maximum over the G heads of the row (adjacent lanes)
             const float pj = jlane && jrow < nvalid ? __builtin_amdgcn_exp2f(x) : 0.0f;
             zl += pj;
+            X.pj = pj;
             if (G >= 2) ahat = max(ahat, __builtin_amdgcn_update_dpp(ahat, ahat, 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
             if (G >= 4) ahat = max(ahat, __builtin_amdgcn_update_dpp(ahat, ahat, 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
             if (G >= 8) ahat = max(ahat, __builtin_amdgcn_update_dpp(ahat, ahat, 0x141, 0xF, 0xF, false));   // row_half_mirror
@@ -174,9 +194,11 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
             for (int gr = 0; gr < KG; ++gr) {
                 const uint32_t ss = (uint32_t)__builtin_amdgcn_ds_bpermute(src[gr], (int)ssw);
                 const uint32_t Fg = (uint32_t)__builtin_amdgcn_ds_bpermute(src[gr], (int)Fw);
+                if (!SHARED) {
 #pragma unroll
-                for (int g = 0; g < G; ++g)
-                    X.p[gr][g] = bits_float((uint32_t)__builtin_amdgcn_ds_bpermute(src[gr] + 4 * g, (int)float_bits(pj)));
+                    for (int g = 0; g < G; ++g)
+                        X.p[SHARED ? 0 : gr][SHARED ? 0 : g] = bits_float((uint32_t)__builtin_amdgcn_ds_bpermute(src[gr] + 4 * g, (int)float_bits(pj)));
+                }
                 const uint32_t hw[4] = {X.hi[gr].x, X.hi[gr].y, X.hi[gr].z, X.hi[gr].w};
                 uint32_t any1 = Fg, any2 = Fg >> 8;   // bit 15 of Fg implies bit 7: stray bits in any1 do no harm
 #pragma unroll
@@ -248,9 +270,43 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
                                  lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
                                  lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int g = 0; g < GA; ++g)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(X.p[gr][g], v[i], acc[g][i]);
+                for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(X.p[SHARED ? 0 : gr][SHARED ? 0 : g], v[i], acc[g][i]);
+        }
+    };
+
+    // shared mode: A leaves the wave's rows of batch bt and their weights in the round's buffer, Fs adds all rows of it
+    auto A = [&](const Batch& X, int bt) {
+        const int buf = bt & 1;
+#pragma unroll
+        for (int gr = 0; gr < KG; ++gr) {
+            uint32_t pa[4], pb[4];
+            assemble8_fill(X.hi[gr].x, X.hi[gr].y, X.mid[gr].x, X.lo[gr].x, X.fill[gr], pa);
+            assemble8_fill(X.hi[gr].z, X.hi[gr].w, X.mid[gr].y, X.lo[gr].y, X.fill[gr], pb);
+            uint32_t* row = sh->v[buf][wave * RB + gr * 8 + r];
+            *reinterpret_cast<uint4*>(row + cl * 4) = make_uint4(pa[0], pa[1], pa[2], pa[3]);
+            *reinterpret_cast<uint4*>(row + 32 + cl * 4) = make_uint4(pb[0], pb[1], pb[2], pb[3]);
+        }
+        if (jlane) sh->p[buf][wave * RB + jrow][jg] = X.pj;
+    };
+    auto Fs = [&](int bt) {
+        const int buf = bt & 1;
+#pragma unroll
+        for (int j = 0; j < kVWaves * KG; ++j) {
+            const uint32_t* row = sh->v[buf][j * 8 + r];
+            const uint4 pa = *reinterpret_cast<const uint4*>(row + cl * 4);
+            const uint4 pb = *reinterpret_cast<const uint4*>(row + 32 + cl * 4);
+            const float v[16] = {lo_half(pa.x), lo_half(pa.y), hi_half(pa.x), hi_half(pa.y),
+                                 lo_half(pa.z), lo_half(pa.w), hi_half(pa.z), hi_half(pa.w),
+                                 lo_half(pb.x), lo_half(pb.y), hi_half(pb.x), hi_half(pb.y),
+                                 lo_half(pb.z), lo_half(pb.w), hi_half(pb.z), hi_half(pb.w)};
+#pragma unroll
+            for (int ga = 0; ga < GA; ++ga) {
+                const float pw = sh->p[buf][j * 8 + r][wave * GA + ga];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[ga][i] = fmaf(pw, v[i], acc[ga][i]);
+            }
         }
     };
 
@@ -281,7 +337,15 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
             D(ring[(k + 1) % R], i + k + 1);
             Lhi(ring[(k + DL) % R], i + k + DL);
             Llg(ring[(k + DL) % R], i + k + DL);
-            F(ring[k], i + k);
+            if (SHARED) {
+                if (i + k < nbatches) {   // the same for every wave of the workgroup
+                    A(ring[k], i + k);
+                    lds_barrier();
+                    Fs(i + k);
+                }
+            } else {
+                F(ring[k], i + k);
+            }
         }
     }
 #pragma unroll
@@ -304,12 +368,14 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
 
 // sum acc over the 8 row lanes of a wave (lanes with the same lane % 8) and z over all lanes; afterwards
 // lanes 0..7 hold the wave's totals for their channel slices and every lane holds the wave's z
-template <int G>
-__device__ __forceinline__ void v_reduce_rows(float (&acc)[G][16], float (&z)[G])
+template <int GA, int G>
+__device__ __forceinline__ void v_reduce_rows(float (&acc)[GA][16], float (&z)[G])
 {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < G; ++g)
         for (int o = 1; o < 64; o <<= 1) z[g] += __shfl_xor(z[g], o);
+#pragma unroll
+    for (int g = 0; g < GA; ++g) {
         for (int o = 8; o < 64; o <<= 1) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[g][i] += __shfl_xor(acc[g][i], o);

@@ -118,6 +118,9 @@ CASES = [
     # longest sequence whose logits it keeps in registers
     ("cfg2-mha-long", 2, dict(B=3, Hq=2, Hkv=2, N=5000), [5000, 4097, 4096], {}),
     ("cfg4-gqa2-long", 4, dict(B=2, Hq=4, Hkv=2, N=4300), [4300, 2048], {}),
+    # groups of four and eight heads over several rounds of the V kernel's shared mode, with a ragged last round
+    ("cfg4-gqa8-long", 4, dict(B=2, Hq=16, Hkv=2, N=2300), [2300, 1029], {}),
+    ("cfg2-gqa4-guard1", 2, dict(B=2, Hq=8, Hkv=2, N=3100), [3100, 65], dict(guard_bits=1)),
 ]
 
 

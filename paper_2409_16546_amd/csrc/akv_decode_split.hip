@@ -287,17 +287,18 @@ __global__ __launch_bounds__(256) void split_select_kernel(DecodeArgs a)
 
 // Workgroup = kVWaves waves, one (sequence, KV head, kVChunk-token chunk); wave w takes the batches of rows
 // w, w + kVWaves, ... of the chunk.  Groups of four or eight query heads run v_rows in its shared mode: every wave
-// fetches and assembles its rows once, the rows pass through LDS, and wave w sums them for its share of the heads.
+// fetches and assembles its rows once, the rows pass through LDS, and the sums over rows for all heads of the group
+// are matrix products on the matrix cores.
 template <int G> constexpr bool v_shared() { return G >= kVWaves; }
 template <int G, bool DEBUG>
 __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 {
     constexpr bool SHARED = v_shared<G>();
-    constexpr int GA = SHARED ? G / kVWaves : G;            // query heads a wave sums for
     constexpr int KG = G >= 8 ? 1 : 2, RB = 8 * KG;         // one lane per (row of the batch, query head): at most 64 / G rows
-    __shared__ float red_s[SHARED ? 1 : kVWaves][G][kD + 1];
+    struct Private { float red[kVWaves][G][kD]; };
+    struct Shared { union { VShare<G, RB> rows; float red[G][kD]; }; };   // the sums are laid down when the last round has been read
+    __shared__ std::conditional_t<SHARED, Shared, Private> lds_s;
     __shared__ float z_s[kVWaves][G];
-    __shared__ std::conditional_t<SHARED, VShare<G, RB>, int> share_s;
     __shared__ int last_s;
 
     const int h = blockIdx.y, b = blockIdx.z, split = blockIdx.x;
@@ -321,27 +322,41 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     float Mg[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) Mg[g] = a.M[size_t(b) * Hq + size_t(h) * G + g];
-    float acc[GA][16], z[G];
+    float acc[SHARED ? 1 : G][SHARED ? 8 : 16], z[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) z[g] = 0.0f;
 #pragma unroll
-    for (int g = 0; g < GA; ++g)
+    for (int g = 0; g < (SHARED ? 1 : G); ++g)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
-    // HI bytes fetched three or four batches ahead: the accumulators of a group of query heads leave room for few waves
-    // per SIMD, so each wave keeps more bytes in flight
+        for (int i = 0; i < (SHARED ? 8 : 16); ++i) acc[g][i] = 0.0f;
+    // HI bytes fetched three or four batches ahead
     constexpr int DL = G == 2 ? 4 : 3;
     const u32x4_t none[1][KG] = {};
-    if constexpr (SHARED)
-        v_rows<G, KG, DEBUG, 0, DL, true, GA>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false, nullptr, 0, &share_s);
-    else
+    if constexpr (SHARED) {
+        v_rows<G, KG, DEBUG, 0, DL, true, true>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false, nullptr, 0, &lds_s.rows);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            for (int o = 1; o < 64; o <<= 1) z[g] += __shfl_xor(z[g], o);
+        // a result tile holds the high parts of the weights in its rows 0 .. G-1 and the low parts in rows G .. 2G-1:
+        // lanes 16 * (G / 4) apart hold the two parts of one (query head, line)
+        float part[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part[i] = (acc[0][i] + __shfl(acc[0][i], (lane + 4 * G) & 63)) * (1.0f / kVWeightScale);
+        __syncthreads();   // every wave is done with the rows of the last round: the same LDS now takes the sums
+        if (lane < 4 * G) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) lds_s.red[4 * (lane >> 4) + i][line_channel(32 * wave + 16 * t + (lane & 15))] = part[4 * t + i];
+        }
+    } else {
         v_rows<G, KG, DEBUG, 0, DL, true>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false);
-    v_reduce_rows<GA>(acc, z);
-    if (r == 0) {
+        v_reduce_rows<G>(acc, z);
+        if (r == 0) {
 #pragma unroll
-        for (int g = 0; g < GA; ++g) {
+            for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) red_s[SHARED ? 0 : wave][SHARED ? wave * GA + g : g][cl * 16 + i] = acc[g][i];
+                for (int i = 0; i < 16; ++i) lds_s.red[wave][g][cl * 16 + i] = acc[g][i];
         }
     }
     if (lane == 0) {
@@ -353,7 +368,11 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
         const int g = idx / (kD + 1), d = idx % (kD + 1);
         float s = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kVWaves; ++w) s += d == kD ? z_s[w][g] : (SHARED && w > 0 ? 0.0f : red_s[SHARED ? 0 : w][g][d]);
+        for (int w = 0; w < kVWaves; ++w) {
+            if (d == kD) s += z_s[w][g];
+            else if constexpr (SHARED) s += w == 0 ? lds_s.red[g][d] : 0.0f;
+            else s += lds_s.red[w][g][d];
+        }
         const size_t hq = size_t(b) * Hq + size_t(h) * G + g;
         if (d < kD) store_agent(&a.partO[(hq * nsplit + split) * kD + d], s);
         else store_agent(&a.partZ[hq * nsplit + split], s);
@@ -393,7 +412,7 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
 // what the register and LDS budgets of split_v_kernel<G> leave room for
 int split_v_workgroups_per_cu(int G)
 {
-    if (G >= kVWaves) return 4;   // shared mode: 16 or 32 sums per lane, 37 KB of LDS
+    if (G >= kVWaves) return 4;   // shared mode: 104 registers, 39 KB of LDS
     return G <= 1 ? 4 : (G <= 2 ? 3 : (G <= 4 ? 2 : 1));
 }
 

@@ -76,13 +76,28 @@ __device__ __forceinline__ void v_prefetch_hi(const DecodeArgs& a, int b, int h,
         for (int gr = 0; gr < KG; ++gr) hi[n][gr] = buf_load_b128(rs_hi, voff + uint32_t(n * batch_stride + gr * 8) * kD);
 }
 
-// LDS of the shared mode of v_rows: the rows all waves of a workgroup assembled in one round (fp16 pairs as
-// assemble8_fill leaves them: words 0..31 the first eight channels of the eight 16-channel slices, words 32..63 the
-// second eight) and the weights of these rows for every query head, in two buffers that alternate by round.
+// LDS of the shared mode of v_rows: the rows all waves of a workgroup assembled in one round, transposed -- line L
+// holds one of the 128 values of a row (as fp16) for every row of the round, so that four consecutive rows of a line
+// are one 8-byte read, the operand layout of the 16x16x16 matrix instruction -- and the weights of these rows, line
+// g the high part and line G + g the low part of query head g's weight (two fp16 numbers whose sum carries 22 bits).
+// Two buffers alternate by round.  Lines are kStride halves apart: 8-byte aligned, neighbouring lines two banks apart.
+// Which channel a line holds: line_channel().
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 template <int G, int RB> struct VShare {
-    alignas(16) uint32_t v[2][kVWaves * RB][64];
-    float p[2][kVWaves * RB][G];
+    static constexpr int kRows = kVWaves * RB;   // rows of a round
+    static constexpr int kStride = kRows + 4;
+    alignas(16) uint16_t vt[2][kD][kStride];
+    alignas(16) uint16_t pt[2][16][kStride];
 };
+// assemble8_fill leaves channels (0,2), (1,3), (4,6), (5,7) of eight in its four words; the lane of channel slice cl
+// stores half hf of word wi of its first eight channels in line 8 * (2 * wi + hf) + cl, of its second eight 64 lines on
+__device__ __forceinline__ int line_channel(int line)
+{
+    const int c = (line & 63) >> 3, cl = line & 7, wi = c >> 1, hf = c & 1;
+    return 16 * cl + 8 * (line >> 6) + (wi & 1) + 4 * (wi >> 1) + 2 * hf;
+}
+constexpr float kVWeightScale = 16384.0f;   // weights are at most 1: scaled by 2^14 their fp16 parts reach down to 2^-38
 // workgroup barrier that waits for this wave's LDS traffic only: the loads from memory that are in flight stay in flight
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -106,20 +121,21 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // NT: the HI bytes are read with the non-temporal hint (measured: it pays in the token-split V kernel, where the logits
 // and the chunk partials of other workgroups share the caches, and costs in the head-per-workgroup kernel); the MID
 // and LO bytes always are (it pays in both).
-// GA < G, sh: the shared mode for groups of query heads.  Every wave of the workgroup still fetches, tests and
-// assembles its own rows, once, but leaves them in LDS with their weights; after a barrier wave w adds ALL rows of
-// the round into acc for the GA query heads w*GA .. w*GA + GA - 1 only.  The arithmetic per row is the same; a lane
-// holds 16*GA sums instead of 16*G, which is what lets twice as many waves be resident.  All waves of the workgroup
-// must call with the same nbatches.
-template <int G, int KG, bool DEBUG, int NPRE, int DL = 2, bool NT = false, int GA = G>
+// SHARED, sh: the shared mode for groups of query heads (the token-split V kernel).  Every wave of the workgroup still
+// fetches, tests and assembles its own rows, once, but leaves them in LDS (transposed) with their weights; after a
+// barrier the sum over the rows of the round, for all query heads at once, is a matrix product on the matrix cores:
+// D[m][line] += sum_rows W[m][row] * V[row][line], wave w taking lines 32 w .. 32 w + 31.  acc then holds the wave's two
+// 16x16 result tiles (four words each: rows 4 * (lane / 16) .. + 3 of W, line 16 * (2 w + tile) + lane % 16), scaled by
+// kVWeightScale.  A lane holds 8 sums instead of 16 * G, the multiply-adds leave the vector ALU.  All waves of the
+// workgroup must call with the same nbatches.
+template <int G, int KG, bool DEBUG, int NPRE, int DL = 2, bool NT = false, bool SHARED = false>
 __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_first, int batch_stride, int nbatches,
-                                       int len, const VRule& vr, const float (&Mg)[G], float (&acc)[GA][16],
+                                       int len, const VRule& vr, const float (&Mg)[G], float (&acc)[SHARED ? 1 : G][SHARED ? 8 : 16],
                                        float (&z)[G], const u32x4_t (&pre)[NPRE > 0 ? NPRE : 1][KG], bool pre_ok,
                                        const float* lds_lg = nullptr, int lds_stride = 0, VShare<G, 8 * KG>* sh = nullptr)
 {
     constexpr int RB = 8 * KG;
-    constexpr bool SHARED = GA != G;
-    static_assert(!SHARED || GA * kVWaves == G, "shared mode: the waves of a workgroup split the query heads of the group");
+    static_assert(!SHARED || (G >= 4 && 2 * G <= 16 && kVWaves * 32 == kD && KG <= 2), "shared mode: high and low parts of all heads are the 16 rows of W; four waves share the 128 lines");
     const int wave = threadIdx.x >> 6;
     // wave-uniform by contract: scalar registers, scalar loop control
     nbatches = __builtin_amdgcn_readfirstlane(nbatches);
@@ -270,45 +286,67 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
                                  lo_half(pb[0]), lo_half(pb[1]), hi_half(pb[0]), hi_half(pb[1]),
                                  lo_half(pb[2]), lo_half(pb[3]), hi_half(pb[2]), hi_half(pb[3])};
 #pragma unroll
-            for (int g = 0; g < GA; ++g)
+            for (int g = 0; g < (SHARED ? 1 : G); ++g)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[g][i] = fmaf(X.p[SHARED ? 0 : gr][SHARED ? 0 : g], v[i], acc[g][i]);
+                for (int i = 0; i < (SHARED ? 8 : 16); ++i) acc[g][i] = fmaf(X.p[SHARED ? 0 : gr][SHARED ? 0 : g], v[i], acc[g][i]);
         }
     };
 
-    // shared mode: A leaves the wave's rows of batch bt and their weights in the round's buffer, Fs adds all rows of it
+    // shared mode: A leaves the wave's rows of batch bt, transposed, and their weights in the round's buffer; Fs is the
+    // wave's share of the matrix product over the rows of the round
     auto A = [&](const Batch& X, int bt) {
         const int buf = bt & 1;
+        uint32_t pa[KG][4], pb[KG][4];
 #pragma unroll
         for (int gr = 0; gr < KG; ++gr) {
-            uint32_t pa[4], pb[4];
-            assemble8_fill(X.hi[gr].x, X.hi[gr].y, X.mid[gr].x, X.lo[gr].x, X.fill[gr], pa);
-            assemble8_fill(X.hi[gr].z, X.hi[gr].w, X.mid[gr].y, X.lo[gr].y, X.fill[gr], pb);
-            uint32_t* row = sh->v[buf][wave * RB + gr * 8 + r];
-            *reinterpret_cast<uint4*>(row + cl * 4) = make_uint4(pa[0], pa[1], pa[2], pa[3]);
-            *reinterpret_cast<uint4*>(row + 32 + cl * 4) = make_uint4(pb[0], pb[1], pb[2], pb[3]);
+            assemble8_fill(X.hi[gr].x, X.hi[gr].y, X.mid[gr].x, X.lo[gr].x, X.fill[gr], pa[gr]);
+            assemble8_fill(X.hi[gr].z, X.hi[gr].w, X.mid[gr].y, X.lo[gr].y, X.fill[gr], pb[gr]);
         }
-        if (jlane) sh->p[buf][wave * RB + jrow][jg] = X.pj;
-    };
-    auto Fs = [&](int bt) {
-        const int buf = bt & 1;
+        // the order of the rows inside a round is free (the weights follow it): the lane's two rows, 8 apart in the
+        // batch, are neighbours in the buffer, so that one 32-bit store lays down both
+        const int row = wave * RB + KG * r;
 #pragma unroll
-        for (int j = 0; j < kVWaves * KG; ++j) {
-            const uint32_t* row = sh->v[buf][j * 8 + r];
-            const uint4 pa = *reinterpret_cast<const uint4*>(row + cl * 4);
-            const uint4 pb = *reinterpret_cast<const uint4*>(row + 32 + cl * 4);
-            const float v[16] = {lo_half(pa.x), lo_half(pa.y), hi_half(pa.x), hi_half(pa.y),
-                                 lo_half(pa.z), lo_half(pa.w), hi_half(pa.z), hi_half(pa.w),
-                                 lo_half(pb.x), lo_half(pb.y), hi_half(pb.x), hi_half(pb.y),
-                                 lo_half(pb.z), lo_half(pb.w), hi_half(pb.z), hi_half(pb.w)};
-#pragma unroll
-            for (int ga = 0; ga < GA; ++ga) {
-                const float pw = sh->p[buf][j * 8 + r][wave * GA + ga];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[ga][i] = fmaf(pw, v[i], acc[ga][i]);
+        for (int wi = 0; wi < 4; ++wi) {
+            if (KG == 2) {
+                *reinterpret_cast<uint32_t*>(&sh->vt[buf][8 * (2 * wi) + cl][row]) = __builtin_amdgcn_perm(pa[KG - 1][wi], pa[0][wi], 0x05040100u);
+                *reinterpret_cast<uint32_t*>(&sh->vt[buf][8 * (2 * wi + 1) + cl][row]) = __builtin_amdgcn_perm(pa[KG - 1][wi], pa[0][wi], 0x07060302u);
+                *reinterpret_cast<uint32_t*>(&sh->vt[buf][64 + 8 * (2 * wi) + cl][row]) = __builtin_amdgcn_perm(pb[KG - 1][wi], pb[0][wi], 0x05040100u);
+                *reinterpret_cast<uint32_t*>(&sh->vt[buf][64 + 8 * (2 * wi + 1) + cl][row]) = __builtin_amdgcn_perm(pb[KG - 1][wi], pb[0][wi], 0x07060302u);
+            } else {
+                sh->vt[buf][8 * (2 * wi) + cl][row] = (uint16_t)pa[0][wi];
+                sh->vt[buf][8 * (2 * wi + 1) + cl][row] = (uint16_t)(pa[0][wi] >> 16);
+                sh->vt[buf][64 + 8 * (2 * wi) + cl][row] = (uint16_t)pb[0][wi];
+                sh->vt[buf][64 + 8 * (2 * wi + 1) + cl][row] = (uint16_t)(pb[0][wi] >> 16);
             }
         }
+        if (jlane) {
+            const float ws = X.pj * kVWeightScale;
+            const _Float16 whi = (_Float16)ws;
+            const _Float16 wlo = (_Float16)(ws - (float)whi);
+            const int wrow = wave * RB + KG * (jrow & 7) + (jrow >> 3);
+            sh->pt[buf][jg][wrow] = __builtin_bit_cast(uint16_t, whi);
+            sh->pt[buf][G + jg][wrow] = __builtin_bit_cast(uint16_t, wlo);
+        }
     };
+    f32x4_t d0 = {0.0f, 0.0f, 0.0f, 0.0f}, d1 = {0.0f, 0.0f, 0.0f, 0.0f};   // the wave's two result tiles
+    auto Fs = [&](int bt) {
+        const int buf = bt & 1;
+        const int n = lane & 15, kq = 4 * (lane >> 4);
+#pragma unroll
+        for (int kb = 0; kb < (kVWaves * RB) / 16; ++kb) {
+            const half4_t w4 = *reinterpret_cast<const half4_t*>(&sh->pt[buf][n][kb * 16 + kq]);
+            const half4_t v0 = *reinterpret_cast<const half4_t*>(&sh->vt[buf][32 * wave + n][kb * 16 + kq]);
+            const half4_t v1 = *reinterpret_cast<const half4_t*>(&sh->vt[buf][32 * wave + 16 + n][kb * 16 + kq]);
+            d0 = __builtin_amdgcn_mfma_f32_16x16x16f16(w4, v0, d0, 0, 0, 0);
+            d1 = __builtin_amdgcn_mfma_f32_16x16x16f16(w4, v1, d1, 0, 0, 0);
+        }
+    };
+    if constexpr (SHARED && 2 * G < 16) {   // the rows of W no head uses stay zero in both buffers (ordered before the first read by the first barrier)
+        for (int idx = threadIdx.x; idx < 2 * (16 - 2 * G) * VShare<G, RB>::kStride; idx += 64 * kVWaves) {
+            const int bf = idx / ((16 - 2 * G) * VShare<G, RB>::kStride), rest = idx % ((16 - 2 * G) * VShare<G, RB>::kStride);
+            sh->pt[bf][2 * G + rest / VShare<G, RB>::kStride][rest % VShare<G, RB>::kStride] = 0;
+        }
+    }
 
     // R = DL + 1 named buffers: round i runs D(i + 1), L(i + DL), F(i); the buffer L fills is the one F emptied in
     // the round before.  The loop is unrolled R times so that every buffer index is a constant.  Loads come back in
@@ -350,6 +388,13 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) z[g] += jg == g ? zl : 0.0f;
+    if (SHARED) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[0][i] = d0[i];
+            acc[0][SHARED ? 4 + i : 0] = d1[i];
+        }
+    }
     if (DEBUG && a.stats) {   // uniform; one set of atomics per wave
         st_need[0] -= st_need[1] + st_need[2];
         unsigned v6[6] = {st_rows[0], st_rows[1], st_rows[2], st_need[0], st_need[1], st_need[2]};
@@ -368,14 +413,12 @@ __device__ __forceinline__ void v_rows(const DecodeArgs& a, int b, int h, int t_
 
 // sum acc over the 8 row lanes of a wave (lanes with the same lane % 8) and z over all lanes; afterwards
 // lanes 0..7 hold the wave's totals for their channel slices and every lane holds the wave's z
-template <int GA, int G>
-__device__ __forceinline__ void v_reduce_rows(float (&acc)[GA][16], float (&z)[G])
+template <int G>
+__device__ __forceinline__ void v_reduce_rows(float (&acc)[G][16], float (&z)[G])
 {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int g = 0; g < G; ++g) {
         for (int o = 1; o < 64; o <<= 1) z[g] += __shfl_xor(z[g], o);
-#pragma unroll
-    for (int g = 0; g < GA; ++g) {
         for (int o = 8; o < 64; o <<= 1) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[g][i] += __shfl_xor(acc[g][i], o);

@@ -125,8 +125,12 @@ def run_both(k, v, q, lens, Ncap=None, dev="cuda:0", path=0, **params):
     topk = params.get("topk", 32)
     dbg = A.DebugBuffers.allocate(gc, topk=topk)
     stats = A.new_stats(dev)
-    out = A.akv_decode_attention(gc, q.to(dev), dbg=dbg, path=path, stats=stats, **params)
+    out = A.akv_decode_attention(gc, q.to(dev), dbg=dbg, path=path, stats=stats, **params).clone()
+    # the same call with nothing exported runs the kernels as a caller gets them (no export code compiled in): the
+    # exports must not change a bit of the result
+    plain = A.akv_decode_attention(gc, q.to(dev), path=path, **params)
     torch.cuda.synchronize()
+    assert torch.equal(plain, out), f"path {path}: the output without exports differs from the one with them"
     r = O.decode_attention(oc, bits(q), **params)
     assert_stats_equal(stats, r, f"path {path}")
     return gc, oc, out, dbg, r

@@ -271,13 +271,14 @@ def test_decode_is_deterministic_and_fp16_output(T):
         assert torch.equal(o16, o1.to(torch.float16))
 
 
-def test_max_len_hint_gives_the_same_result(T):
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (8, 2), (8, 1)], ids=["mha", "gqa4", "gqa8"])
+def test_max_len_hint_gives_the_same_result(T, Hq, Hkv):
     from paper_2409_16546_amd import workloads, binding as A
-    say("decode: max_len hint bounds the launch, same result")
-    w = workloads.make(2, B=2, Hq=2, Hkv=2, N=700)
+    say(f"decode: max_len hint bounds the launch, same result (Hq {Hq}, Hkv {Hkv})")
+    w = workloads.make(2, B=2, Hq=Hq, Hkv=Hkv, N=700)
     gc = T.gpu_cache(w.k, w.v, [700, 300], w.Hq, 4096)
     q = w.q.to(DEV)
-    for path in (1, 2):
+    for path in ((1, 2) if Hq // Hkv <= 4 else (2,)):
         o1 = A.akv_decode_attention(gc, q, path=path).clone()
         o2 = A.akv_decode_attention(gc, q, max_len=700, path=path).clone()
         torch.cuda.synchronize()

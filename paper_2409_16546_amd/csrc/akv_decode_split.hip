@@ -329,8 +329,9 @@ __global__ __launch_bounds__(64 * kVWaves) void split_v_kernel(DecodeArgs a)
     for (int g = 0; g < (SHARED ? 1 : G); ++g)
 #pragma unroll
         for (int i = 0; i < (SHARED ? 8 : 16); ++i) acc[g][i] = 0.0f;
-    // HI bytes fetched three or four batches ahead
-    constexpr int DL = G == 2 ? 4 : 3;
+    // HI bytes fetched three or four batches ahead in the private mode (few waves per SIMD: each keeps more bytes in
+    // flight), two in the shared mode (four waves per SIMD; three and four measured 1.5 % and 3 % slower)
+    constexpr int DL = SHARED ? 2 : (G == 2 ? 4 : 3);
     const u32x4_t none[1][KG] = {};
     if constexpr (SHARED) {
         v_rows<G, KG, DEBUG, 0, DL, true, true>(a, b, h, c0 + wave * RB, RB * kVWaves, vchunk / (RB * kVWaves), len, vr, Mg, acc, z, none, false, nullptr, 0, &lds_s.rows);
